@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Benchmark of the ATB BFP16 x BF16 GEMM on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload square8192] [--tiles T_MA,T_MC,T_K,T_N]
+
+One "step" is one pass of the whole hot path over one synthetic problem: a
+single atb_gemm_run (tile decomposition, B-tile fetch, A sub-tile fetch, BFP16
+decode, MFMA microkernels, sub-tile switches, epilogue).  Inputs (A already
+quantised to BFP16 by atb_bfp16_quantize, B bf16) are resident in HBM before
+the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="square8192")
+    ap.add_argument("--tiles", default="", help="T_MA,T_MC,T_K,T_N (default: the selector's pick)")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the per-instance sweep")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--cpu-rows", type=int, default=1024, help="rows of C the oracle computes for the CPU baseline")
+    return ap.parse_args()
+
+
+def time_plan(plan, A_bfp, B, C, steps, warmup):
+    """Returns (wall seconds for `steps` launches, mean kernel ms from HIP events on the launch stream)."""
+    import torch
+    for _ in range(warmup):
+        plan.run(A_bfp, B, C)
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()                      # current stream = the stream the kernels are launched on
+    for _ in range(steps):
+        plan.run(A_bfp, B, C)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, ev0.elapsed_time(ev1) / steps
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); nothing is sharded across GPUs.", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2511_16041_amd as atb
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
+        sys.exit(1)
+    atb.lib()                                         # fail loudly if the extension is missing
+    cfg = workloads.CONFIGS[args.workload]
+    M, N, K = cfg.M, cfg.N, cfg.K
+    A, Bb = workloads.make_inputs(cfg)
+    A_dev = torch.from_numpy(A).cuda()
+    A_bfp = atb.bfp16_quantize(A_dev)
+    del A_dev
+    B = torch.from_numpy(Bb.view(np.int16)).view(torch.bfloat16).cuda()
+    C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    torch.cuda.synchronize()
+
+    ranked = atb.select_tiles(M, N, K)
+    if args.tiles:
+        tiles = tuple(int(x) for x in args.tiles.split(","))
+    else:
+        tiles = ranked[0].tiles()
+    flop = 2.0 * M * N * K
+
+    plan = atb.Gemm(M, N, K, *tiles)
+    info = plan.launch_info()
+    wall, kernel_ms = time_plan(plan, A_bfp, B, C, args.steps, args.warmup)
+    ms_per_step = wall / args.steps * 1e3
+    tflops = flop / (wall / args.steps) / 1e12
+    kernel_tflops = flop / (kernel_ms * 1e-3) / 1e12
+    plan.close()
+
+    sweep = []
+    if not args.no_sweep:
+        pred = {c.tiles(): c.pred_flops / 1e12 for c in ranked}
+        for t in atb.instances():
+            if t[1] != tiles[1] and (M * N) // (t[1] * t[3]) > 65536:
+                continue
+            p = atb.Gemm(M, N, K, *t)
+            _, kms = time_plan(p, A_bfp, B, C, max(5, args.steps // 5), 3)
+            p.close()
+            sweep.append({"tiles": list(t), "rho": t[1] // t[0], "tflops": round(flop / (kms * 1e-3) / 1e12, 1),
+                          "model_tflops": round(pred.get(t, 0.0), 1)})
+        sym = [s for s in sweep if s["rho"] == 1 and s["tiles"][1:] == list(tiles[1:])]
+        best_atb = max([s for s in sweep if s["rho"] > 1 and s["tiles"][1:] == list(tiles[1:])],
+                       key=lambda s: s["tflops"], default=None)
+    else:
+        sym, best_atb = [], None
+
+    out = {
+        "metric": "TFLOPS (BFP16xBF16 GEMM, 8192^3) + % of bf16 MFMA peak; ATB vs symmetric speedup",
+        "value": round(tflops, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "M": M, "N": N, "K": K,
+                   "tiles": {"T_MA": tiles[0], "T_MC": tiles[1], "T_K": tiles[2], "T_N": tiles[3]},
+                   "rho": tiles[1] // tiles[0], "workgroups": info.workgroups, "threads": info.threads,
+                   "lds_bytes": info.lds_bytes, "a_format": "BFP16 (int8 mantissa + shared uint8 exponent per 8)",
+                   "accumulate": "fp32", "out": "bf16"},
+        "pct_of_bf16_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
+        "roofline": {"bound": "mfma", "achieved": round(kernel_tflops, 2), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(kernel_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "kernel": "atb_gemm_kernel", "kernel_ms": round(kernel_ms, 4),
+                     "algorithmic_flop_per_launch": flop},
+    }
+    if sweep:
+        out["rho_sweep"] = sweep
+        if sym and best_atb:
+            out["atb_vs_symmetric"] = round(best_atb["tflops"] / sym[0]["tflops"], 4)
+
+    if not args.no_cpu:
+        import oracle
+        lay = atb.bfp16_layout(M, K)
+        raw = A_bfp.cpu().numpy()
+        nrows = min(args.cpu_rows, M)
+        mant = raw[: M * lay.ldm].reshape(M, lay.ldm)[:nrows, :K].view(np.int8).copy()
+        expo = raw[lay.exp_off: lay.exp_off + M * lay.lde].reshape(M, lay.lde)[:nrows, : K // 8].copy()
+        t0 = time.perf_counter()
+        _, _, threads = oracle.gemm(mant, expo, Bb)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(2.0 * nrows * N * K / dt / 1e12, 5), "unit": "TFLOP/s",
+                               "cores": int(threads), "kind": "oracle",
+                               "sample": f"first {nrows} of {M} rows of C (all {N} columns, full K={K}), "
+                                         f"{dt:.1f} s; fp64 accumulate"}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

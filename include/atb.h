@@ -1,0 +1,176 @@
+/*
+ * libatb -- BFP16 x BF16 GEMM with asymmetric tile buffering (ATB) for AMD
+ * MI355X (gfx950), after "Can Asymmetric Tile Buffering Be Beneficial?"
+ * (arXiv 2511.16041).
+ *
+ * C ABI.  Every pointer argument says whether it is HOST or DEVICE memory.
+ * The caller owns every buffer; the library allocates host memory only (in
+ * atb_gemm_create) and never device memory.  No function throws, aborts or
+ * synchronises the device; every function that can fail returns an
+ * atb_status.  Streams are hipStream_t values passed as void* (NULL = the
+ * default stream).
+ *
+ * Operation (Sec. 1 and Sec. 3 of the paper):  C = A x B with A in R^{MxK},
+ * B in R^{KxN}, C in R^{MxN}.  A is stored in BFP16 (Sec. 2.4: blocks of 8
+ * values along K share one 8-bit exponent and keep an 8-bit mantissa each),
+ * B and C are bf16, accumulation is fp32.  The kernel is output-stationary
+ * (Sec. 3.1): each workgroup owns one T_MC x T_N tile of C for the whole
+ * reduction; per K-step of T_K it keeps a T_K x T_N tile of B resident and
+ * streams A through in sub-tiles of T_MA <= T_MC rows (rho = T_MC / T_MA
+ * "kernel switches" per K-step, Sec. 5).  T_MA == T_MC is symmetric tiling.
+ *
+ * BFP16 values (the reading of Sec. 2.4 used throughout):
+ *     a[i][k] = m[i][k] * 2^(E[i][k/8] - 133),  m int8 in [-127, 127],
+ *     E uint8 = 127 + max over the block of floor(log2 |x|)  (0 for a zero block),
+ *     m = clamp(round_to_nearest_even(x * 2^(133 - E)), -127, 127).
+ *
+ * Device layout of an A_bfp buffer (atb_bfp16_layout gives the numbers):
+ *     mantissa plane  int8  [M][ldm]  at byte 0,        ldm = round_up(K, 16)
+ *     exponent plane  uint8 [M][lde]  at byte exp_off,  lde = round_up(K/8, 16),
+ *                                     exp_off = round_up(M * ldm, 256)
+ *     total bytes = round_up(exp_off + M * lde, 256)
+ *   Padding bytes of the mantissa plane (k >= K) MUST be zero; padding bytes
+ *   of the exponent plane are ignored.  9 bytes per 8 elements as in the
+ *   paper's packed bfp16ebs8, but planar so that all loads are aligned.
+ * B: bf16, row-major K x N, leading dimension N.  C: bf16, row-major M x N,
+ * leading dimension N.  A_bfp, B and C must be 16-byte aligned.
+ */
+#ifndef ATB_H
+#define ATB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum atb_status {
+    ATB_OK = 0,
+    ATB_ERR_INVALID_ARG = 1, /* NULL pointer, non-positive size, K % 8 != 0, misaligned buffer */
+    ATB_ERR_BAD_TILE = 2,    /* T_MC % T_MA != 0, or (T_MA,T_MC,T_K,T_N) is not a compiled instance */
+    ATB_ERR_LDS_BUDGET = 3,  /* the tile's A and B buffers exceed the 160 KiB LDS of a CU */
+    ATB_ERR_REG_BUDGET = 4,  /* the T_MC x T_N fp32 C tile exceeds the accumulator registers */
+    ATB_ERR_HIP = 5,         /* a HIP call failed (no device, bad launch); see atb_last_hip_error */
+    ATB_ERR_NOMEM = 6        /* host allocation failed */
+} atb_status;
+
+/* Static string for a status code. Never NULL. */
+const char *atb_status_string(atb_status s);
+
+/* hipError_t value of the most recent failing HIP call on this thread (0 if none). */
+int atb_last_hip_error(void);
+
+/* ------------------------------------------------------------------ GEMM */
+
+typedef struct atb_gemm atb_gemm; /* opaque plan, HOST memory */
+
+/* Plan C[M][N] = A_bfp[M][K] x B[K][N] with the tile factors of Sec. 3
+ * (T_MA rows of A buffered per sub-tile, T_MC x T_N C tile, T_K reduction
+ * step).  Touches no device.  Requirements: M, N, K >= 1, K % 8 == 0,
+ * T_MC % T_MA == 0, and the factors must name a compiled instance (see
+ * atb_instance_count / atb_instance_get).  M and N need not be multiples of
+ * the tile (edge tiles are masked); K need not be a multiple of T_K.
+ * On success *out is a new plan, else *out = NULL. */
+atb_status atb_gemm_create(atb_gemm **out, int64_t M, int64_t N, int64_t K,
+                           int T_MA, int T_MC, int T_K, int T_N);
+
+/* Launch the planned GEMM on `hip_stream`; returns after the launch (async).
+ * A_bfp: DEVICE, layout above, read-only.  B_bf16: DEVICE, K x N bf16,
+ * read-only.  C_bf16: DEVICE, M x N bf16, fully overwritten.  Inputs must be
+ * finite.  Reports launch-time errors only. */
+atb_status atb_gemm_run(const atb_gemm *g, const void *A_bfp, const void *B_bf16,
+                        void *C_bf16, void *hip_stream);
+
+void atb_gemm_destroy(atb_gemm *g);
+
+/* Launch geometry of a plan, for benches and tests: number of workgroups,
+ * threads per workgroup, static LDS bytes per workgroup. Any pointer may be NULL. */
+atb_status atb_gemm_launch_info(const atb_gemm *g, int64_t *workgroups, int *threads, int *lds_bytes);
+
+/* The compiled (T_MA, T_MC, T_K, T_N) instances. */
+int atb_instance_count(void);
+atb_status atb_instance_get(int index, int *T_MA, int *T_MC, int *T_K, int *T_N);
+
+/* ----------------------------------------------------------------- BFP16 */
+
+typedef struct atb_bfp16_layout_t {
+    int64_t ldm;      /* bytes between mantissa rows */
+    int64_t lde;      /* bytes between exponent rows */
+    int64_t exp_off;  /* byte offset of the exponent plane */
+    int64_t bytes;    /* total size of the buffer */
+} atb_bfp16_layout_t;
+
+/* Layout of an A_bfp buffer for an M x K matrix (K % 8 == 0). */
+atb_status atb_bfp16_layout(int64_t M, int64_t K, atb_bfp16_layout_t *out);
+
+/* Total bytes of an A_bfp buffer; 0 on invalid arguments. */
+size_t atb_bfp16_bytes(int64_t M, int64_t K);
+
+/* Quantise A_f32_dev (DEVICE, fp32, M x K, row pitch lda elements, lda >= K,
+ * 16-byte aligned rows: lda % 4 == 0) into A_bfp_dev (DEVICE, layout above,
+ * atb_bfp16_bytes(M,K) bytes; padding is written as zero).  Async on
+ * hip_stream.  Inputs must be finite.  Bit-exact against the definition
+ * in the header comment (Sec. 2.4 reading). */
+atb_status atb_bfp16_quantize(const float *A_f32_dev, int64_t lda, void *A_bfp_dev,
+                              int64_t M, int64_t K, void *hip_stream);
+
+/* Decode an A_bfp buffer to bf16 (DEVICE, M x K, leading dimension K); exact.
+ * For inspection and tests; the GEMM decodes inside its own kernel. */
+atb_status atb_bfp16_decode(const void *A_bfp_dev, void *A_bf16_dev, int64_t M, int64_t K,
+                            void *hip_stream);
+
+/* ------------------------------------------------- model and tile selector */
+
+/* Machine constants of the paper's performance model (Secs. 3 and 5). */
+typedef struct atb_hw_params {
+    double peak_core_flops;   /* Perf_core^peak: one core (XDNA2) / one CU (MI355X), flop/s */
+    int    n_core;            /* N_core */
+    int    array_rows;        /* cores sharing a B tile: L2 tile is array_rows*T_MC x array_cols*T_N (Eq. 2) */
+    int    array_cols;
+    double bw_offchip;        /* BW_offchip, byte/s */
+    double buffer_bytes;      /* S of Eq. (1): L1 (XDNA2) or LDS (MI355X) per core */
+    double acc_bytes;         /* MI355X only: accumulator-register bytes per core; 0 = C lives in `buffer_bytes` */
+    double clock_hz;
+    double delta_cycles;      /* delta: cost of one microkernel switch (Sec. 5) */
+    double eta, eps, II;      /* Eff_micro(T_K) = eta T_K / (eps + eta II T_K), Eq. (12) */
+    double a_bytes, b_bytes, c_bytes; /* bytes per element of A, B, C moved from off-chip */
+    double a_buf_bytes, b_buf_bytes;  /* bytes per element of A, B as buffered (Eq. 1); 0 = same as above */
+    int    n_b_buffers;       /* B buffers in Eq. (1): the paper uses 2 */
+} atb_hw_params;
+
+/* Fill *hw with the paper's XDNA2 constants (Secs. 2.4, 3.2, 5; precision
+ * Config 1 byte costs) or with this library's MI355X constants. */
+void atb_hw_params_xdna2(atb_hw_params *hw);
+void atb_hw_params_mi355x(atb_hw_params *hw);
+
+typedef struct atb_choice {
+    int T_MA, T_MC, T_K, T_N;
+    int rho;               /* T_MC / T_MA */
+    int feasible;          /* buffer (and accumulator) constraints hold */
+    double ai;             /* AI_array, Eq. (2)  [flop/byte] */
+    double ai_core;        /* AI_rho, Sec. 3.1 */
+    double buffer_bytes;   /* left side of Eq. (1) (C term dropped when acc_bytes > 0) */
+    double acc_bytes;      /* 4 * T_MC * T_N when acc_bytes > 0 in hw, else 0 */
+    double eff_micro;      /* Eq. (12) */
+    double eff_core;       /* Eq. (15) */
+    double mem_bound;      /* AI_array * BW_offchip, flop/s */
+    double compute_bound;  /* Eff_core * Perf_core^peak * N_core, flop/s */
+    double pred_flops;     /* Eq. (11): min of the two */
+} atb_choice;
+
+/* Evaluate the model (Eqs. 1, 2, 11, 12, 15) for one set of tile factors.
+ * hw == NULL means MI355X.  Pure host arithmetic. */
+atb_status atb_model_eval(int64_t M, int64_t N, int64_t K, int T_MA, int T_MC, int T_K, int T_N,
+                          const atb_hw_params *hw, atb_choice *out);
+
+/* Rank the compiled instances for a problem by predicted throughput
+ * (infeasible ones last).  Writes min(capacity, count) entries to `ranked`
+ * (HOST) and the number of instances to *count.  ranked[0] is the pick. */
+atb_status atb_select_tiles(int64_t M, int64_t N, int64_t K, const atb_hw_params *hw,
+                            atb_choice *ranked, int capacity, int *count);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ATB_H */

@@ -1,0 +1,157 @@
+// C ABI of libatb (see include/atb.h): argument checking, plans, launches.
+#include <cstdlib>
+#include <new>
+
+#include "atb_internal.h"
+
+struct atb_gemm {
+    int64_t M, N, K;
+    int instance;
+    atb_bfp16_layout_t layout;
+    atb::GemmParams proto;   // everything but the pointers
+};
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+atb_status hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return ATB_OK;
+    g_last_hip_error = (int)e;
+    return ATB_ERR_HIP;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace
+
+extern "C" const char *atb_status_string(atb_status s)
+{
+    switch (s) {
+        case ATB_OK: return "ok";
+        case ATB_ERR_INVALID_ARG: return "invalid argument";
+        case ATB_ERR_BAD_TILE: return "tile factors are not a compiled instance (or T_MC % T_MA != 0)";
+        case ATB_ERR_LDS_BUDGET: return "tile buffers exceed the LDS of a compute unit";
+        case ATB_ERR_REG_BUDGET: return "C tile exceeds the accumulator registers";
+        case ATB_ERR_HIP: return "HIP call failed";
+        case ATB_ERR_NOMEM: return "out of host memory";
+    }
+    return "unknown status";
+}
+
+extern "C" int atb_last_hip_error(void) { return g_last_hip_error; }
+
+extern "C" int atb_instance_count(void) { return atb::instance_count(); }
+
+extern "C" atb_status atb_instance_get(int index, int *T_MA, int *T_MC, int *T_K, int *T_N)
+{
+    if (index < 0 || index >= atb::instance_count()) return ATB_ERR_INVALID_ARG;
+    const atb::Instance &x = atb::instance(index);
+    if (T_MA) *T_MA = x.T_MA;
+    if (T_MC) *T_MC = x.T_MC;
+    if (T_K) *T_K = x.T_K;
+    if (T_N) *T_N = x.T_N;
+    return ATB_OK;
+}
+
+extern "C" atb_status atb_bfp16_layout(int64_t M, int64_t K, atb_bfp16_layout_t *out)
+{
+    if (!out || M < 1 || K < 8 || (K % 8) != 0) return ATB_ERR_INVALID_ARG;
+    out->ldm = atb::round_up(K, 16);
+    out->lde = atb::round_up(K / 8, 16);
+    out->exp_off = atb::round_up(M * out->ldm, 256);
+    out->bytes = atb::round_up(out->exp_off + M * out->lde, 256);
+    return ATB_OK;
+}
+
+extern "C" size_t atb_bfp16_bytes(int64_t M, int64_t K)
+{
+    atb_bfp16_layout_t l;
+    if (atb_bfp16_layout(M, K, &l) != ATB_OK) return 0;
+    return (size_t)l.bytes;
+}
+
+extern "C" atb_status atb_bfp16_quantize(const float *A, int64_t lda, void *A_bfp, int64_t M, int64_t K,
+                                         void *stream)
+{
+    atb_bfp16_layout_t l;
+    if (!A || !A_bfp || atb_bfp16_layout(M, K, &l) != ATB_OK || lda < K || (lda % 4) != 0) return ATB_ERR_INVALID_ARG;
+    if (!aligned16(A) || !aligned16(A_bfp)) return ATB_ERR_INVALID_ARG;
+    if (M * (l.ldm / 16) > (int64_t)0x7FFFFFFF * 256) return ATB_ERR_INVALID_ARG;
+    int8_t *Am = static_cast<int8_t *>(A_bfp);
+    uint8_t *Ae = static_cast<uint8_t *>(A_bfp) + l.exp_off;
+    return hip_status(atb::launch_quantize(A, lda, Am, Ae, M, K, l.ldm, l.lde, static_cast<hipStream_t>(stream)));
+}
+
+extern "C" atb_status atb_bfp16_decode(const void *A_bfp, void *A_bf16, int64_t M, int64_t K, void *stream)
+{
+    atb_bfp16_layout_t l;
+    if (!A_bfp || !A_bf16 || atb_bfp16_layout(M, K, &l) != ATB_OK) return ATB_ERR_INVALID_ARG;
+    if (!aligned16(A_bfp) || !aligned16(A_bf16)) return ATB_ERR_INVALID_ARG;
+    const int8_t *Am = static_cast<const int8_t *>(A_bfp);
+    const uint8_t *Ae = static_cast<const uint8_t *>(A_bfp) + l.exp_off;
+    return hip_status(atb::launch_decode(Am, Ae, static_cast<uint16_t *>(A_bf16), M, K, l.ldm, l.lde,
+                                         static_cast<hipStream_t>(stream)));
+}
+
+extern "C" atb_status atb_gemm_create(atb_gemm **out, int64_t M, int64_t N, int64_t K,
+                                      int T_MA, int T_MC, int T_K, int T_N)
+{
+    if (!out) return ATB_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (M < 1 || N < 1 || K < 8 || (K % 8) != 0) return ATB_ERR_INVALID_ARG;
+    // 32-bit element offsets inside the kernel: keep every plane below 2^31 elements
+    if (M > (1 << 24) || N > (1 << 24) || K > (1 << 24) || M * N >= ((int64_t)1 << 31) ||
+        M * atb::round_up(K, 16) >= ((int64_t)1 << 31) || K * N >= ((int64_t)1 << 31))
+        return ATB_ERR_INVALID_ARG;
+    if (T_MA < 1 || T_MC < 1 || T_K < 1 || T_N < 1) return ATB_ERR_INVALID_ARG;
+    if (T_MC % T_MA != 0) return ATB_ERR_BAD_TILE;
+    // budgets of one CU: A (double-buffered, bf16) and B (double-buffered, bf16) in 160 KiB of LDS,
+    // the fp32 C tile in 4 waves x 256 accumulator registers
+    if ((int64_t)4 * T_MC * T_N > 256 * 1024) return ATB_ERR_REG_BUDGET;
+    if ((int64_t)2 * 2 * T_MA * T_K + (int64_t)2 * 2 * T_K * T_N > 160 * 1024) return ATB_ERR_LDS_BUDGET;
+    const int idx = atb::find_instance(T_MA, T_MC, T_K, T_N);
+    if (idx < 0) return ATB_ERR_BAD_TILE;
+
+    atb_gemm *g = new (std::nothrow) atb_gemm;
+    if (!g) return ATB_ERR_NOMEM;
+    g->M = M; g->N = N; g->K = K;
+    g->instance = idx;
+    atb_bfp16_layout(M, K, &g->layout);
+    atb::GemmParams &p = g->proto;
+    p.Am = nullptr; p.Ae = nullptr; p.B = nullptr; p.C = nullptr;
+    p.M = (int)M; p.N = (int)N; p.K = (int)K;
+    p.ldm = (int)g->layout.ldm;
+    p.lde = (int)g->layout.lde;
+    p.tiles_m = (int)((M + T_MC - 1) / T_MC);
+    p.tiles_n = (int)((N + T_N - 1) / T_N);
+    p.group_m = 8;
+    *out = g;
+    return ATB_OK;
+}
+
+extern "C" atb_status atb_gemm_run(const atb_gemm *g, const void *A_bfp, const void *B, void *C, void *stream)
+{
+    if (!g || !A_bfp || !B || !C) return ATB_ERR_INVALID_ARG;
+    if (!aligned16(A_bfp) || !aligned16(B) || !aligned16(C)) return ATB_ERR_INVALID_ARG;
+    atb::GemmParams p = g->proto;
+    p.Am = static_cast<const int8_t *>(A_bfp);
+    p.Ae = static_cast<const uint8_t *>(A_bfp) + g->layout.exp_off;
+    p.B = static_cast<const uint16_t *>(B);
+    p.C = static_cast<uint16_t *>(C);
+    return hip_status(atb::instance(g->instance).launch(p, static_cast<hipStream_t>(stream)));
+}
+
+extern "C" void atb_gemm_destroy(atb_gemm *g) { delete g; }
+
+extern "C" atb_status atb_gemm_launch_info(const atb_gemm *g, int64_t *workgroups, int *threads, int *lds_bytes)
+{
+    if (!g) return ATB_ERR_INVALID_ARG;
+    const atb::Instance &x = atb::instance(g->instance);
+    const int64_t total = (int64_t)g->proto.tiles_m * g->proto.tiles_n;
+    if (workgroups) *workgroups = (total + 7) / 8 * 8;
+    if (threads) *threads = x.threads;
+    if (lds_bytes) *lds_bytes = x.lds_bytes;
+    return ATB_OK;
+}

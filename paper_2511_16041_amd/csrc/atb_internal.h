@@ -1,0 +1,45 @@
+// Internal declarations shared by the translation units of libatb.
+// Not part of the public C ABI (see include/atb.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "atb.h"
+
+namespace atb {
+
+// Arguments of one GEMM launch (device pointers are never dereferenced on the host).
+struct GemmParams {
+    const int8_t *Am;    // mantissa plane  [M][ldm]
+    const uint8_t *Ae;   // exponent plane  [M][lde]
+    const uint16_t *B;   // bf16 [K][N]
+    uint16_t *C;         // bf16 [M][N]
+    int M, N, K;
+    int ldm, lde;
+    int tiles_m, tiles_n;   // number of C tiles along M and N
+    int group_m;            // tile rows that are walked together (rasterisation)
+};
+
+// One compiled kernel instance.
+struct Instance {
+    int T_MA, T_MC, T_K, T_N;
+    int wave_m, wave_n;     // wave grid inside the workgroup
+    int threads;            // wave_m * wave_n * 64
+    int lds_bytes;          // static LDS of the kernel
+    hipError_t (*launch)(const GemmParams &p, hipStream_t stream);
+};
+
+int instance_count();
+const Instance &instance(int i);
+// index of the instance with these factors, or -1
+int find_instance(int T_MA, int T_MC, int T_K, int T_N);
+
+hipError_t launch_quantize(const float *A, int64_t lda, int8_t *Am, uint8_t *Ae, int64_t M, int64_t K,
+                           int64_t ldm, int64_t lde, hipStream_t stream);
+hipError_t launch_decode(const int8_t *Am, const uint8_t *Ae, uint16_t *out, int64_t M, int64_t K,
+                         int64_t ldm, int64_t lde, hipStream_t stream);
+
+static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+
+}  // namespace atb

@@ -1,0 +1,138 @@
+// Analytical model of arXiv 2511.16041 (Secs. 3 and 5) and the tile-factor
+// selector built on it.  Pure host arithmetic.
+//
+//   AI_rho   = 2 / (a/T_N + b/T_MC + c/K)                                  Sec. 3.1
+//   buffer   = (2a/rho) T_MC T_K + n_B b T_K T_N + c T_MC T_N <= S         Eq. (1)
+//   AI_array = 2 / (a/(cols T_N) + b/(rows T_MC) + c/K)                    Eq. (2)
+//   Eff_micro(T_K) = eta T_K / (eps + eta II T_K)                          Eq. (12)
+//   Eff_core = 1 / (1/Eff_micro + delta rho Peak_core / (2 T_MC T_N T_K))  Eq. (15)
+//   Perf     = min(AI_array BW, Eff_core Peak_core N_core)                 Eq. (11)
+//
+// On MI355X the C tile lives in accumulator registers, so Eq. (1) splits in
+// two: the A and B terms are charged to the LDS (with the bytes per element
+// they occupy there, bf16 after the in-kernel decode) and the C term to the
+// accumulator file (fp32).  "rows x cols" is the patch of C tiles that the
+// workgroups resident on one XCD share through its L2, the counterpart of the
+// 4 x 8 core array that shares L2 tiles by broadcast in the paper.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <vector>
+
+#include "atb_internal.h"
+
+extern "C" void atb_hw_params_xdna2(atb_hw_params *hw)
+{
+    if (!hw) return;
+    std::memset(hw, 0, sizeof *hw);
+    hw->clock_hz = 1.8e9;
+    hw->peak_core_flops = 2.0 * 512.0 * 1.8e9;   // 8x8x8 MAC unit, Sec. 2.4
+    hw->n_core = 32;
+    hw->array_rows = 4;                          // Sec. 3.2
+    hw->array_cols = 8;
+    hw->bw_offchip = 65e9;                       // Sec. 5
+    hw->buffer_bytes = 63.0 * 1024.0;            // Sec. 3.2
+    hw->acc_bytes = 0.0;                         // C is buffered in L1
+    hw->delta_cycles = 50.0;                     // Sec. 5
+    hw->eta = 0.03;                              // fitted to Table 1's Eff_micro column
+    hw->eps = 1.0;
+    hw->II = 1.2;
+    hw->a_bytes = 2.0;                           // precision Config 1: A bf16, B BFP16, C bf16
+    hw->b_bytes = 1.25;                          // Sec. 3.1 quotes 1.25 B per BFP16 element
+    hw->c_bytes = 2.0;
+    hw->a_buf_bytes = 0.0;
+    hw->b_buf_bytes = 0.0;
+    hw->n_b_buffers = 2;
+}
+
+extern "C" void atb_hw_params_mi355x(atb_hw_params *hw)
+{
+    if (!hw) return;
+    std::memset(hw, 0, sizeof *hw);
+    hw->clock_hz = 2.4e9;
+    hw->peak_core_flops = 2.5e15 / 256.0;        // dense bf16 MFMA peak per CU
+    hw->n_core = 256;
+    hw->array_rows = 8;                          // C tiles co-resident on one XCD (32 CUs): 8 x 4 patch
+    hw->array_cols = 4;
+    hw->bw_offchip = 8.0e12;                     // HBM3E
+    hw->buffer_bytes = 160.0 * 1024.0;           // LDS per CU
+    hw->acc_bytes = 256.0 * 1024.0;              // 4 waves x 256 accumulator VGPRs x 64 lanes x 4 B
+    hw->delta_cycles = 300.0;                    // one workgroup barrier + pipeline drain per sub-tile (measured)
+    hw->eta = 0.05;
+    hw->eps = 1.0;
+    hw->II = 1.3;
+    hw->a_bytes = 1.125;                         // A BFP16: 9 bytes per 8 elements
+    hw->b_bytes = 2.0;
+    hw->c_bytes = 2.0;
+    hw->a_buf_bytes = 2.25;                      // decoded bf16 in LDS, 16 B pad per 128 B row
+    hw->b_buf_bytes = 2.25;
+    hw->n_b_buffers = 2;
+}
+
+extern "C" atb_status atb_model_eval(int64_t M, int64_t N, int64_t K, int T_MA, int T_MC, int T_K, int T_N,
+                                     const atb_hw_params *hw_in, atb_choice *out)
+{
+    if (!out || M < 1 || N < 1 || K < 1 || T_MA < 1 || T_MC < 1 || T_K < 1 || T_N < 1) return ATB_ERR_INVALID_ARG;
+    if (T_MC % T_MA != 0) return ATB_ERR_BAD_TILE;
+    atb_hw_params hw;
+    if (hw_in) hw = *hw_in; else atb_hw_params_mi355x(&hw);
+    if (hw.peak_core_flops <= 0 || hw.n_core < 1 || hw.array_rows < 1 || hw.array_cols < 1 || hw.clock_hz <= 0 ||
+        hw.eta <= 0 || hw.II <= 0)
+        return ATB_ERR_INVALID_ARG;
+
+    const double a = hw.a_bytes, b = hw.b_bytes, c = hw.c_bytes;
+    const double ab = hw.a_buf_bytes > 0 ? hw.a_buf_bytes : a;
+    const double bb = hw.b_buf_bytes > 0 ? hw.b_buf_bytes : b;
+    const int nb = hw.n_b_buffers > 0 ? hw.n_b_buffers : 2;
+    const double rho = (double)T_MC / (double)T_MA;
+
+    atb_choice r;
+    std::memset(&r, 0, sizeof r);
+    r.T_MA = T_MA; r.T_MC = T_MC; r.T_K = T_K; r.T_N = T_N;
+    r.rho = T_MC / T_MA;
+    r.ai_core = 2.0 / (a / T_N + b / T_MC + c / (double)K);
+    r.ai = 2.0 / (a / ((double)hw.array_cols * T_N) + b / ((double)hw.array_rows * T_MC) + c / (double)K);
+    const bool c_in_regs = hw.acc_bytes > 0.0;
+    r.buffer_bytes = (2.0 * ab / rho) * T_MC * T_K + nb * bb * T_K * T_N + (c_in_regs ? 0.0 : c * T_MC * T_N);
+    r.acc_bytes = c_in_regs ? 4.0 * T_MC * T_N : 0.0;
+    r.feasible = (r.buffer_bytes <= hw.buffer_bytes) && (!c_in_regs || r.acc_bytes <= hw.acc_bytes);
+    r.eff_micro = hw.eta * T_K / (hw.eps + hw.eta * hw.II * T_K);
+    const double delta_s = hw.delta_cycles / hw.clock_hz;
+    r.eff_core = 1.0 / (1.0 / r.eff_micro + delta_s * rho * hw.peak_core_flops / (2.0 * T_MC * (double)T_N * T_K));
+    r.mem_bound = r.ai * hw.bw_offchip;
+    r.compute_bound = r.eff_core * hw.peak_core_flops * hw.n_core;
+    if (c_in_regs) {
+        // One workgroup per CU at a time: the last, partly filled wave of tiles idles CUs, and tiles
+        // that hang over the matrix edge compute on padding.
+        const double tm = std::ceil((double)M / T_MC), tn = std::ceil((double)N / T_N);
+        const double tiles = tm * tn;
+        const double waves = std::ceil(tiles / hw.n_core);
+        const double fill = tiles / (waves * hw.n_core);
+        const double useful = ((double)M * (double)N) / (tm * T_MC * tn * T_N);
+        r.compute_bound *= fill * useful;
+    }
+    r.pred_flops = std::min(r.mem_bound, r.compute_bound);
+    *out = r;
+    return ATB_OK;
+}
+
+extern "C" atb_status atb_select_tiles(int64_t M, int64_t N, int64_t K, const atb_hw_params *hw,
+                                       atb_choice *ranked, int capacity, int *count)
+{
+    if (M < 1 || N < 1 || K < 1 || capacity < 0 || (capacity > 0 && !ranked)) return ATB_ERR_INVALID_ARG;
+    std::vector<atb_choice> all;
+    for (int i = 0; i < atb::instance_count(); ++i) {
+        const atb::Instance &x = atb::instance(i);
+        atb_choice ch;
+        atb_status st = atb_model_eval(M, N, K, x.T_MA, x.T_MC, x.T_K, x.T_N, hw, &ch);
+        if (st != ATB_OK) return st;
+        all.push_back(ch);
+    }
+    std::stable_sort(all.begin(), all.end(), [](const atb_choice &x, const atb_choice &y) {
+        if (x.feasible != y.feasible) return x.feasible > y.feasible;
+        return x.pred_flops > y.pred_flops;
+    });
+    if (count) *count = (int)all.size();
+    for (int i = 0; i < capacity && i < (int)all.size(); ++i) ranked[i] = all[i];
+    return ATB_OK;
+}

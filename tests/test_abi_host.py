@@ -1,0 +1,135 @@
+"""CPU-only tests of libatb: the library loads, exports every symbol the header
+declares, validates arguments without touching a device, lays BFP16 out as
+documented, and its model / selector agree with the oracle of the paper's model."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2511_16041_amd as atb
+from oracle import model as om
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "atb.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(atb_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = atb.lib()
+    names = _declared_symbols()
+    assert len(names) >= 16
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(atb.EXPORTS) == names
+
+
+def test_status_strings():
+    L = atb.lib()
+    seen = {L.atb_status_string(i) for i in range(7)}
+    assert len(seen) == 7 and all(s for s in seen)
+    assert L.atb_status_string(99) is not None
+
+
+def test_instances_and_create_validation():
+    inst = atb.instances()
+    assert (256, 256, 64, 256) in inst and (64, 256, 64, 256) in inst and (32, 64, 64, 64) in inst
+    for (a, c, k, n) in inst:
+        assert c % a == 0 and k % 16 == 0
+    L = atb.lib()
+    h = ctypes.c_void_p()
+
+    def create(M, N, K, *t):
+        return L.atb_gemm_create(ctypes.byref(h), M, N, K, *t)
+
+    assert create(256, 256, 256, 32, 64, 64, 64) == 0 and h.value
+    wg, th, lds = ctypes.c_int64(), ctypes.c_int(), ctypes.c_int()
+    assert L.atb_gemm_launch_info(h, ctypes.byref(wg), ctypes.byref(th), ctypes.byref(lds)) == 0
+    assert wg.value == 16 and th.value == 256 and 0 < lds.value <= 160 * 1024
+    L.atb_gemm_destroy(h)
+    assert create(0, 256, 256, 32, 64, 64, 64) == 1 and not h.value          # M < 1
+    assert create(256, 256, 252, 32, 64, 64, 64) == 1                         # K % 8
+    assert create(256, 256, 256, 48, 64, 64, 64) == 2                         # T_MC % T_MA
+    assert create(256, 256, 256, 64, 64, 32, 64) == 2                         # not compiled
+    assert create(256, 256, 256, 512, 512, 64, 256) == 4                      # C tile > accumulators
+    assert create(256, 256, 256, 256, 256, 512, 64) == 3                      # A + B > LDS
+    assert L.atb_gemm_create(None, 1, 1, 8, 32, 64, 64, 64) == 1
+    assert L.atb_gemm_run(None, None, None, None, None) == 1
+    L.atb_gemm_destroy(None)                                                  # no-op
+
+
+def test_bfp16_layout():
+    for (M, K) in [(256, 256), (3000, 4104), (1, 8), (7, 24)]:
+        lay = atb.bfp16_layout(M, K)
+        assert lay.ldm % 16 == 0 and K <= lay.ldm < K + 16
+        assert lay.lde % 16 == 0 and K // 8 <= lay.lde < K // 8 + 16
+        assert lay.exp_off % 256 == 0 and lay.exp_off >= M * lay.ldm
+        assert lay.bytes % 256 == 0 and lay.bytes >= lay.exp_off + M * lay.lde
+        assert atb.bfp16_bytes(M, K) == lay.bytes
+        # last 16-byte mantissa chunk of a row has its two exponents inside the exponent row
+        assert (lay.ldm - 16) // 8 + 1 < lay.lde + 1
+    assert atb.bfp16_bytes(4, 12) == 0 and atb.bfp16_bytes(0, 8) == 0
+    # 9 bytes per 8 elements, up to padding
+    lay = atb.bfp16_layout(8192, 8192)
+    assert lay.bytes == 8192 * 8192 * 9 // 8
+
+
+def test_model_matches_oracle_in_paper_mode():
+    hw = atb.hw_params("xdna2")
+    assert hw.n_core == 32 and hw.array_rows == 4 and hw.array_cols == 8
+    peak = om.peak_core_flops(512, 1.8e9)
+    assert hw.peak_core_flops == pytest.approx(peak)
+    cases = [(2048, 2048, 4096, 64, 64, 64, 128), (2048, 2048, 4480, 16, 64, 224, 64),
+             (4096, 2048, 4096, 32, 128, 64, 128), (4096, 2048, 4096, 128, 128, 8, 128)]
+    for (M, N, K, T_MA, T_MC, T_K, T_N) in cases:
+        ch = atb.model_eval(M, N, K, T_MA, T_MC, T_K, T_N, hw)
+        a, b, c = hw.a_bytes, hw.b_bytes, hw.c_bytes
+        rho = T_MC // T_MA
+        assert ch.rho == rho
+        assert ch.ai_core == pytest.approx(om.ai_rho(T_MC, T_N, K, a, b, c), rel=1e-12)
+        assert ch.ai == pytest.approx(om.ai_array(T_MC, T_N, K, a, b, c, 4, 8), rel=1e-12)
+        assert ch.buffer_bytes == pytest.approx(om.buffer_bytes(T_MA, T_MC, T_K, T_N, a, b, c), rel=1e-12)
+        em = om.eff_micro(T_K, hw.eta, hw.eps, hw.II)
+        assert ch.eff_micro == pytest.approx(em, rel=1e-12)
+        ec = om.eff_core(T_MC, T_K, T_N, rho, peak, em, hw.delta_cycles / hw.clock_hz)
+        assert ch.eff_core == pytest.approx(ec, rel=1e-12)
+        perf, mem, comp = om.perf_array(ch.ai, hw.bw_offchip, ec, peak, 32)
+        assert ch.mem_bound == pytest.approx(mem, rel=1e-12)
+        assert ch.compute_bound == pytest.approx(comp, rel=1e-12)
+        assert ch.pred_flops == pytest.approx(perf, rel=1e-12)
+        assert ch.feasible == int(ch.buffer_bytes <= 63 * 1024)
+    # Table 2, Config 1, 128x64x128 rho=4: AI_array 410, memory bound 26.6 TFLOP/s
+    ch = atb.model_eval(4096, 2048, 4096, 32, 128, 64, 128, hw)
+    assert round(ch.ai) == 410 and ch.mem_bound / 1e12 == pytest.approx(26.6, abs=0.1)
+
+
+def test_model_mi355x_mode_and_selector():
+    hw = atb.hw_params("mi355x")
+    assert hw.n_core == 256 and hw.buffer_bytes == 160 * 1024 and hw.acc_bytes == 256 * 1024
+    assert hw.peak_core_flops * hw.n_core == pytest.approx(2.5e15)
+    ch = atb.model_eval(8192, 8192, 8192, 64, 256, 64, 256)          # hw = NULL -> MI355X
+    ch2 = atb.model_eval(8192, 8192, 8192, 64, 256, 64, 256, hw)
+    assert ch.pred_flops == ch2.pred_flops and ch.feasible == 1
+    assert ch.acc_bytes == 4 * 256 * 256
+    # C lives in registers: the LDS term has no C share
+    ab, bb = hw.a_buf_bytes, hw.b_buf_bytes
+    assert ch.buffer_bytes == pytest.approx(2 * ab * 64 * 64 + 2 * bb * 64 * 256)
+    # Eq. (15) ordering: at fixed C tile and T_K, larger rho never raises the compute bound
+    prev = None
+    for T_MA in (256, 128, 64, 32):
+        c = atb.model_eval(8192, 8192, 8192, T_MA, 256, 64, 256, hw)
+        if prev is not None:
+            assert c.eff_core < prev.eff_core and c.buffer_bytes < prev.buffer_bytes
+        prev = c
+    ranked = atb.select_tiles(8192, 8192, 8192)
+    assert len(ranked) == len(atb.instances())
+    assert ranked[0].feasible == 1 and ranked[0].T_MC == 256
+    assert all(ranked[i].pred_flops >= ranked[i + 1].pred_flops
+               for i in range(len(ranked) - 1) if ranked[i + 1].feasible)
+    small = atb.select_tiles(256, 256, 256)
+    assert small[0].T_MC == 64                        # 16 small tiles beat one big tile on 256 CUs
+    assert atb.lib().atb_select_tiles(0, 1, 8, None, None, 0, None) == 1

@@ -1,0 +1,155 @@
+"""GPU ATB GEMM vs the oracle (runs on an MI355X, through the C ABI).
+
+Acceptance: |C_gpu - C_ref| <= 2^-7 * sum_k |a||b| + 1e-6 for every element;
+bit-exact where fp32 accumulation is exact in any order."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2511_16041_amd as atb
+import workloads
+from helpers import bf16_tensor_bits, bits_to_bf16_tensor, pack_a_bfp
+
+pytestmark = pytest.mark.gpu
+
+BIG = [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256), (32, 256, 64, 256)]
+SMALL = [(64, 64, 64, 64), (32, 64, 64, 64)]
+
+
+def _run(mant, expo, Bb, tiles, poison=True):
+    import torch
+    M, K = mant.shape
+    N = Bb.shape[1]
+    lay = atb.bfp16_layout(M, K)
+    A_dev = torch.from_numpy(pack_a_bfp(mant, expo, lay)).cuda()
+    B_dev = bits_to_bf16_tensor(Bb, "cuda")
+    C_dev = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda") if poison else None
+    g = atb.Gemm(M, N, K, *tiles)
+    C_dev = g.run(A_dev, B_dev, C_dev)
+    torch.cuda.synchronize()
+    g.close()
+    return bf16_tensor_bits(C_dev)
+
+
+def _check(Cg_bits, C_ref, T, what):
+    got = oracle.bf16_to_double(Cg_bits)
+    assert not np.isnan(got).any(), f"{what}: unwritten or NaN outputs"
+    err = np.abs(got - oracle.bf16_to_double(C_ref))
+    tol = oracle.tolerance(T)
+    bad = err > tol
+    assert not bad.any(), f"{what}: {bad.sum()} elements out of tolerance, worst ratio {np.max(err / tol):.3g} at {np.unravel_index(np.argmax(err / tol), err.shape)}"
+    return float(np.max(err / tol))
+
+
+def test_instances_cover_the_tests():
+    assert set(BIG + SMALL) == set(atb.instances())
+
+
+@pytest.mark.parametrize("tiles", SMALL + BIG)
+def test_small256_config(tiles):
+    print(f"gemm small256 tiles={tiles}", flush=True)
+    A, Bb = workloads.make_inputs(workloads.CONFIGS["small256"])
+    mant, expo = oracle.quantize(A)
+    C_ref, T, _ = oracle.gemm(mant, expo, Bb)
+    _check(_run(mant, expo, Bb, tiles), C_ref, T, f"small256 {tiles}")
+
+
+@pytest.mark.parametrize("tiles", SMALL + BIG)
+@pytest.mark.parametrize("shape", [(300, 500, 264), (257, 263, 72), (33, 20, 8), (1, 1, 8), (520, 516, 136), (300, 499, 64)])
+def test_ragged_shapes(tiles, shape):
+    """Several tiles plus ragged M and N tails, a K tail of 8, N not a multiple of 8 or of 4."""
+    M, N, K = shape
+    print(f"gemm ragged {shape} tiles={tiles}", flush=True)
+    A, Bb = workloads.make_inputs(workloads.CONFIGS["ragged"], M=M, N=N, K=K)
+    mant, expo = oracle.quantize(A)
+    C_ref, T, _ = oracle.gemm(mant, expo, Bb)
+    _check(_run(mant, expo, Bb, tiles), C_ref, T, f"ragged {shape} {tiles}")
+
+
+@pytest.mark.parametrize("tiles", SMALL + BIG)
+def test_exact_inputs_bitwise(tiles):
+    """Small-integer inputs: fp32 accumulation is exact in any order, so every instance
+    (every rho) must equal the oracle bit for bit."""
+    print(f"gemm exact tiles={tiles}", flush=True)
+    A, Bb = workloads.small_integer_inputs(300, 260, 200, seed=5)
+    mant, expo = oracle.quantize(A)
+    C_ref, _, _ = oracle.gemm(mant, expo, Bb)
+    assert np.array_equal(_run(mant, expo, Bb, tiles), C_ref)
+
+
+@pytest.mark.parametrize("tiles", [(32, 64, 64, 64), (64, 256, 64, 256), (32, 256, 64, 256)])
+def test_identity_and_permutation(tiles):
+    print(f"gemm identity tiles={tiles}", flush=True)
+    rng = np.random.default_rng(11)
+    K = 320
+    A, _ = workloads.make_inputs(workloads.CONFIGS["mlp"], M=290, N=8, K=K)
+    mant, expo = oracle.quantize(A)
+    dec = oracle.decode(mant, expo)
+    perm = rng.permutation(K)
+    P = np.zeros((K, K), np.float32)
+    P[perm, np.arange(K)] = 1.0
+    got = oracle.bf16_to_double(_run(mant, expo, workloads.fp32_to_bf16_bits(P), tiles))
+    assert np.array_equal(got, dec[:, perm])          # decode is exact, products with 1 are exact
+    # A = identity: C = B bit for bit
+    Bb = workloads.fp32_to_bf16_bits(rng.standard_normal((K, 300)).astype(np.float32))
+    mi, ei = oracle.quantize(np.eye(K, dtype=np.float32))
+    assert np.array_equal(_run(mi, ei, Bb, tiles), Bb)
+
+
+def test_deterministic_and_rho_independent():
+    """Same kernel twice: bitwise equal.  Different rho at the same C tile and T_K use the same
+    per-element accumulation order (k ascending in MFMA slices of 16), so they agree bitwise too."""
+    A, Bb = workloads.make_inputs(workloads.CONFIGS["small256"], M=512, N=512, K=512)
+    mant, expo = oracle.quantize(A)
+    ref = None
+    for tiles in BIG:
+        c1 = _run(mant, expo, Bb, tiles)
+        c2 = _run(mant, expo, Bb, tiles)
+        assert np.array_equal(c1, c2)
+        if ref is None:
+            ref = c1
+        assert np.array_equal(ref, c1), tiles
+
+
+def test_block_exponent_stress():
+    """Outliers x2^8 raise the shared exponent (other mantissas underflow), clamped +-127 mantissas,
+    zero blocks and large exponent spread inside one row."""
+    rng = np.random.default_rng(3)
+    M, N, K = 130, 96, 256
+    A = rng.standard_normal((M, K)).astype(np.float32)
+    A[rng.random((M, K)) < 0.05] *= 256.0
+    A[:, 64:72] = 0.0
+    A[5] *= np.float32(2.0 ** -20)
+    A[6] *= np.float32(2.0 ** 20)
+    A[7, ::8] = 3.999
+    Bb = workloads.fp32_to_bf16_bits((rng.random((K, N)) * 2 - 1).astype(np.float32))
+    mant, expo = oracle.quantize(A)
+    assert (np.abs(mant) == 127).any()
+    C_ref, T, _ = oracle.gemm(mant, expo, Bb)
+    for tiles in [(32, 64, 64, 64), (64, 256, 64, 256)]:
+        _check(_run(mant, expo, Bb, tiles), C_ref, T, f"stress {tiles}")
+
+
+def test_end_to_end_with_gpu_quantizer():
+    """fp32 A -> atb_bfp16_quantize -> atb_gemm_run, against oracle quantise + GEMM."""
+    import torch
+    A, Bb = workloads.make_inputs(workloads.CONFIGS["ragged"], M=300, N=504, K=264)
+    mant, expo = oracle.quantize(A)
+    C_ref, T, _ = oracle.gemm(mant, expo, Bb)
+    A_bfp = atb.bfp16_quantize(torch.from_numpy(A).cuda())
+    g = atb.Gemm(300, 504, 264, 64, 256, 64, 256)
+    C = g.run(A_bfp, bits_to_bf16_tensor(Bb, "cuda"))
+    torch.cuda.synchronize()
+    _check(bf16_tensor_bits(C), C_ref, T, "end to end")
+
+
+def test_run_rejects_bad_arguments():
+    import ctypes
+    import torch
+    g = atb.Gemm(64, 64, 64, 32, 64, 64, 64)
+    buf = torch.zeros(4096 * 4, dtype=torch.uint8, device="cuda")
+    p = ctypes.c_void_p(buf.data_ptr())
+    L = atb.lib()
+    assert L.atb_gemm_run(g._h, None, p, p, None) == 1
+    assert L.atb_gemm_run(g._h, ctypes.c_void_p(buf.data_ptr() + 2), p, p, None) == 1      # misaligned
+    g.close()

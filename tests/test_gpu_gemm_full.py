@@ -1,0 +1,61 @@
+"""Full-size workloads in the launch configuration bench.py times: sampled rows of C against the
+oracle (the oracle computes whole rows one by one), plus the exactness property at full size."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2511_16041_amd as atb
+import workloads
+from helpers import bf16_tensor_bits, bits_to_bf16_tensor, unpack_a_bfp
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    ("square4096", [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256)]),
+    ("square8192", [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256), (32, 256, 64, 256)]),
+    ("mlp", [(256, 256, 64, 256), (64, 256, 64, 256)]),
+    ("ragged", [(256, 256, 64, 256), (64, 256, 64, 256), (32, 64, 64, 64)]),
+]
+
+
+def _sample_rows(M, rng, n=40):
+    edge = [0, 1, 31, 32, 63, 64, 255, 256, M - 257, M - 256, M - 65, M - 33, M - 2, M - 1]
+    rows = sorted(set([r for r in edge if 0 <= r < M] + list(rng.integers(0, M, size=n))))
+    return np.array(rows, dtype=np.int64)
+
+
+@pytest.mark.parametrize("name,tile_list", CASES)
+def test_full_size_sampled_rows(name, tile_list):
+    import torch
+    cfg = workloads.CONFIGS[name]
+    print(f"full-size {name}: generating", flush=True)
+    A, Bb = workloads.make_inputs(cfg)
+    M, K = A.shape
+    N = Bb.shape[1]
+    A_bfp = atb.bfp16_quantize(torch.from_numpy(A).cuda())
+    torch.cuda.synchronize()
+    lay = atb.bfp16_layout(M, K)
+    gm, ge, pad = unpack_a_bfp(A_bfp.cpu().numpy(), M, K, lay)
+    print(f"full-size {name}: oracle quantise", flush=True)
+    mant, expo = oracle.quantize(A)
+    assert np.array_equal(gm, mant) and np.array_equal(ge, expo) and not pad.any()    # quantiser bit-exact at full size
+    del A, gm, ge
+    rows = _sample_rows(M, np.random.default_rng(1))
+    print(f"full-size {name}: oracle gemm on {rows.size} rows", flush=True)
+    C_ref, T, _ = oracle.gemm(mant, expo, Bb, rows=rows)
+    ref = oracle.bf16_to_double(C_ref)
+    tol = oracle.tolerance(T)
+    B_dev = bits_to_bf16_tensor(Bb, "cuda")
+    rows_t = torch.from_numpy(rows).cuda()
+    for tiles in tile_list:
+        print(f"full-size {name}: tiles {tiles}", flush=True)
+        C = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        g = atb.Gemm(M, N, K, *tiles)
+        g.run(A_bfp, B_dev, C)
+        torch.cuda.synchronize()
+        assert not torch.isnan(C).any().item(), f"{name} {tiles}: unwritten outputs"
+        got = oracle.bf16_to_double(bf16_tensor_bits(C[rows_t]))
+        err = np.abs(got - ref)
+        assert not (err > tol).any(), f"{name} {tiles}: worst ratio {np.max(err / tol):.3g}"
+        g.close()
+        del C
