@@ -25,13 +25,14 @@
  *     m = clamp(round_to_nearest_even(x * 2^(133 - E)), -127, 127).
  *
  * Device layout of an A_bfp buffer (atb_bfp16_layout gives the numbers):
- *     mantissa plane  int8  [M][ldm]  at byte 0,        ldm = round_up(K, 16)
- *     exponent plane  uint8 [M][lde]  at byte exp_off,  lde = round_up(K/8, 16),
+ *     mantissa plane  int8  [M][ldm]  at byte 0,        ldm = round_up(K, 128)
+ *     exponent plane  uint8 [M][lde]  at byte exp_off,  lde = ldm / 8,
  *                                     exp_off = round_up(M * ldm, 256)
  *     total bytes = round_up(exp_off + M * lde, 256)
  *   Padding bytes of the mantissa plane (k >= K) MUST be zero; padding bytes
  *   of the exponent plane are ignored.  9 bytes per 8 elements as in the
- *   paper's packed bfp16ebs8, but planar so that all loads are aligned.
+ *   paper's packed bfp16ebs8 (plus row padding), but planar so that all loads are
+ *   aligned and no K-step of the kernel ever leaves a row.
  * B: bf16, row-major K x N, leading dimension N.  C: bf16, row-major M x N,
  * leading dimension N.  A_bfp, B and C must be 16-byte aligned.
  */

@@ -58,8 +58,8 @@ extern "C" atb_status atb_instance_get(int index, int *T_MA, int *T_MC, int *T_K
 extern "C" atb_status atb_bfp16_layout(int64_t M, int64_t K, atb_bfp16_layout_t *out)
 {
     if (!out || M < 1 || K < 8 || (K % 8) != 0) return ATB_ERR_INVALID_ARG;
-    out->ldm = atb::round_up(K, 16);
-    out->lde = atb::round_up(K / 8, 16);
+    out->ldm = atb::round_up(K, 128);
+    out->lde = out->ldm / 8;
     out->exp_off = atb::round_up(M * out->ldm, 256);
     out->bytes = atb::round_up(out->exp_off + M * out->lde, 256);
     return ATB_OK;
@@ -103,7 +103,7 @@ extern "C" atb_status atb_gemm_create(atb_gemm **out, int64_t M, int64_t N, int6
     if (M < 1 || N < 1 || K < 8 || (K % 8) != 0) return ATB_ERR_INVALID_ARG;
     // 32-bit element offsets inside the kernel: keep every plane below 2^31 elements
     if (M > (1 << 24) || N > (1 << 24) || K > (1 << 24) || M * N >= ((int64_t)1 << 31) ||
-        M * atb::round_up(K, 16) >= ((int64_t)1 << 31) || K * N >= ((int64_t)1 << 31))
+        M * atb::round_up(K, 128) >= ((int64_t)1 << 31) || K * N >= ((int64_t)1 << 31))
         return ATB_ERR_INVALID_ARG;
     if (T_MA < 1 || T_MC < 1 || T_K < 1 || T_N < 1) return ATB_ERR_INVALID_ARG;
     if (T_MC % T_MA != 0) return ATB_ERR_BAD_TILE;

@@ -57,7 +57,7 @@ struct Shape {
     static constexpr int NM = PER * KS * NTW;     // MFMAs per wave per microkernel
     // LDS pitches in bytes.  The pad de-phases the banks for the fragment reads.
     static constexpr int PA = T_K * 2 + 16;
-    static constexpr int PB = T_N * 2 + 64;
+    static constexpr int PB = T_N * 2;            // B rows are not padded: an XOR swizzle of the 16-byte chunks avoids the bank conflicts
     static constexpr int A_BYTES = T_MA * PA;
     static constexpr int B_BYTES = T_K * PB;
     static constexpr int LDS_BYTES = 2 * A_BYTES + 2 * B_BYTES;
@@ -71,11 +71,13 @@ struct Shape {
     static constexpr int B_PER_THREAD = B_CHUNKS / NT;
     static constexpr int B_CPR = T_N / 8;         // chunks per B row
     static_assert(T_MC % T_MA == 0, "rho must be an integer");
-    static_assert(PF >= 1 && PF <= 4, "prefetch distance");
+    static_assert(PF >= 2 && (2 * RHO) % PF == 0, "prefetch distance: at least 2 (fetch and decode overlap), dividing two K-steps of sub-tiles");
+    static_assert(128 % T_K == 0 && T_K % 32 == 0, "T_K must divide the 128-byte row padding of the mantissa plane; exponent dwords stay aligned");
     static_assert(T_MA % 32 == 0 && T_N % (32 * WN) == 0 && T_K % 16 == 0, "MFMA 32x32x16 granularity");
     static_assert(MT % WM == 0 && SMT % WM == 0, "every sub-tile must feed every wave row equally");
     static_assert(A_CHUNKS % NT == 0 && NT % A_CPR == 0, "A staging must split evenly over the threads");
     static_assert(B_CHUNKS % NT == 0 && NT % B_CPR == 0, "B staging must split evenly over the threads");
+    static_assert(B_CPR >= 8, "the B swizzle needs 8 chunks per row");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
     static_assert(MTW * NTW * 16 <= 256, "C tile must fit the accumulator registers");
 };
@@ -95,17 +97,70 @@ constexpr int kOutOfRange = (int)0x80000000;     // a byte offset no buffer of o
 
 #define ATB_FENCE() __builtin_amdgcn_sched_barrier(0)
 
+// Developer ablation switches (timing experiments only; results are wrong when non-zero):
+// 1 no decode arithmetic, 2 B fragments read once, 4 global loads once, 8 no LDS stores,
+// 16 no A-fragment reads after the first band, 32 no MFMA, 64 no barrier,
+// 128 global loads never advance (always the first K-step: cache-hot), 256 no A loads, 512 no B loads.
+#ifndef ATB_ABLATE
+#define ATB_ABLATE 0
+#endif
+
+// Cycle stamps for kernel tuning; compiled out of the library (ATB_TRACE is defined only by the
+// developer's own timing harness, which also supplies atb_trace_buf).
+#ifdef ATB_TRACE
+__device__ unsigned long long atb_trace_acc[16];
+#define ATB_TRACE_DECL unsigned long long trace_prev = 0, trace_sum[8] = {}
+#define ATB_STAMP(id)                                                              \
+    do {                                                                           \
+        if (blockIdx.x == 0 && threadIdx.x < 64) {                                 \
+            unsigned long long now = __builtin_amdgcn_s_memtime();                 \
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                     \
+            trace_sum[id] += now - trace_prev;                                     \
+            trace_prev = now;                                                      \
+        }                                                                          \
+    } while (0)
+#define ATB_TRACE_FLUSH()                                                          \
+    do {                                                                           \
+        if (blockIdx.x == 0 && threadIdx.x == 0)                                   \
+            for (int i = 0; i < 8; ++i) atb_trace_acc[i] = trace_sum[i];           \
+    } while (0)
+#else
+#define ATB_TRACE_DECL
+#define ATB_STAMP(id) do { } while (0)
+#define ATB_TRACE_FLUSH() do { } while (0)
+#endif
+
 // The per-workgroup state of one C tile.  Everything is indexed with compile-time constants after
 // inlining, so the arrays live in registers (acc in AccVGPRs).
+//
+// Time line (g = kt*RHO + s numbers the A sub-tiles):
+//   A sub-tile g   : fetched from memory in phase g-PF into register set g % PF, decoded into LDS
+//                    buffer g % 2 during phase g-1, consumed by the microkernel of phase g.
+//   B tile kt      : fetched in the first phase of K-step kt-2, written to LDS buffer kt % 2 in the
+//                    last phase of K-step kt-2, read into the waves' fragment registers during the
+//                    last band of K-step kt-1 (each fragment right after its last use), consumed in
+//                    K-step kt.
+// The K loop is unrolled by two so that every buffer and register-set index is a constant.
 template <class S, bool VEC>
 struct TileKernel {
     const GemmParams &p;
     Rsrc rs;
-    char *a_lds[2];
-    char *b_lds[2];
     int tid, lane, wm, wn, m0, n0;
-    // per-thread staging coordinates (chunk i adds a compile-time multiple of rows)
-    int a_row, a_q, b_row, b_c;
+    // LDS byte addresses of this thread's staging writes and fragment reads, per buffer
+    char *a_wr[2], *b_wr[2];
+    const char *a_rd[2], *b_rd[2][2];  // b_rd[buffer][parity of the column band]
+    char *b_req[2];                    // LDS byte address of this wave's first 1 KiB B request, per buffer
+    // Byte offsets of this thread's global loads relative to the current K-step.  They never
+    // change: the K-step advance is applied to the (scalar) buffer descriptors instead, base up and
+    // size down, so the hardware range check keeps masking rows >= M of A and rows >= K of B, and no
+    // vector register that a memory instruction has just read is written right after it.
+    int a_moff[S::RHO][S::A_PER_THREAD], a_eoff[S::RHO][S::A_PER_THREAD], b_off[S::B_PER_THREAD];
+    int b_col[S::B_PER_THREAD];        // first column of request i's chunk (only used when !VEC)
+    const int8_t *am_ptr;              // start of the K-step the next A fetch belongs to
+    const uint8_t *ae_ptr;
+    const uint16_t *b_ptr;             // start of the K-step the next B fetch belongs to
+    int am_left, ae_left, b_left;      // bytes from those starts to the end of the planes
+    int e_shift;                       // bit position of this thread's exponent byte(s) in the loaded dword
 
     floatx16 acc[S::MTW][S::NTW];
     bf16x8 bfrag[S::KS][S::NTW];       // this wave's slice of the resident B tile
@@ -115,25 +170,70 @@ struct TileKernel {
     intx4 b_raw[S::B_PER_THREAD];
     unsigned dec[4];                   // bf16 pairs of the BFP16 block being decoded
     int shift;
+    ATB_TRACE_DECL;
 
     ATB_DEV TileKernel(const GemmParams &p_, char *lds, int m0_, int n0_) : p(p_), m0(m0_), n0(n0_)
     {
-        a_lds[0] = lds;
-        a_lds[1] = lds + S::A_BYTES;
-        b_lds[0] = lds + 2 * S::A_BYTES;
-        b_lds[1] = b_lds[0] + S::B_BYTES;
         tid = threadIdx.x;
         lane = tid & 63;
         const int wave = tid >> 6;
         wm = wave % S::WM;
         wn = wave / S::WM;
-        a_row = tid / S::A_CPR;
-        a_q = tid % S::A_CPR;
-        b_row = tid / S::B_CPR;
-        b_c = tid % S::B_CPR;
-        rs.am = __builtin_amdgcn_make_buffer_rsrc(const_cast<int8_t *>(p.Am), 0, p.M * p.ldm, kRsrcFlags);
-        rs.ae = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(p.Ae), 0, p.M * p.lde, kRsrcFlags);
-        rs.b = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(p.B), 0, p.K * p.N * 2, kRsrcFlags);
+        const int a_row = tid / S::A_CPR, a_q = tid % S::A_CPR;
+        e_shift = ((a_q * (S::ACE / 8)) & 3) * 8;
+        // B staging.  The tile is row-major in LDS ([k][n], no padding).  The wave's request i fills
+        // the 1 KiB of the tile that starts at (wave*B_PER_THREAD + i) KiB, lane l the 16-byte slot
+        // l of it.  Chunk c of row k is stored at chunk position c ^ ((k & 3) << 1) of its row, so
+        // that the four rows a transposing read touches fall into different banks.
+        const int slot0 = __builtin_amdgcn_readfirstlane(wave) * S::B_PER_THREAD * 64;
+        const int blk = lane >> 4, j = lane & 15, r = j >> 2;
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            char *a_base = lds + b * S::A_BYTES;
+            char *b_base = lds + 2 * S::A_BYTES + b * S::B_BYTES;
+            a_wr[b] = a_base + a_row * S::PA + a_q * (S::ACE * 2);
+            b_req[b] = b_base + slot0 * 16;
+            b_wr[b] = b_req[b] + lane * 16;
+            // A fragment: lane l reads row l%32 of a band, k = ks*16 + 8*(l/32) .. +7
+            a_rd[b] = a_base + (wm * 32 + (lane & 31)) * S::PA + (lane >> 5) * 16;
+            // B fragment through ds_read_b64_tr_b16: within each group of 16 lanes, lane i addresses
+            // 4 consecutive columns of row i/4 (8 bytes, half a chunk), and lane j receives column j
+            // of those 4 rows.  For rows 2, 3 (mod 4) the swizzle flips bit 2 of the chunk index,
+            // which is the parity of the 32-column band: one base address per parity.
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const int chunk = 4 * (wn * S::NTW + e) + 2 * (blk & 1) + ((j & 3) >> 1);
+                b_rd[b][e] = b_base + (8 * (blk >> 1) + r) * S::PB + ((chunk ^ (r << 1)) * 16) + (j & 1) * 8;
+            }
+        }
+        am_ptr = p.Am;
+        ae_ptr = p.Ae;
+        b_ptr = p.B;
+        am_left = p.M * p.ldm;
+        ae_left = p.M * p.lde;
+        b_left = p.K * p.N * 2;
+        remake_a();
+        remake_b();
+        // Offsets of sub-tile 0 / K-step 0.  Rows >= M lie beyond the end of the planes and read as
+        // zero; k never leaves a row because ldm is a multiple of 128 and of T_K (the mantissa bytes
+        // between K and ldm are zero by the layout's contract).
+#pragma unroll
+        for (int sub = 0; sub < S::RHO; ++sub)
+#pragma unroll
+            for (int i = 0; i < S::A_PER_THREAD; ++i) {
+                const int grow = m0 + sub * S::T_MA + a_row + i * (S::NT / S::A_CPR);
+                a_moff[sub][i] = grow * p.ldm + a_q * S::ACE;
+                a_eoff[sub][i] = grow * p.lde + ((a_q * (S::ACE / 8)) & ~3);
+            }
+        // B rows >= K lie beyond the end of B and read as zero; columns >= N wrap into the next row
+        // and only feed output columns that are never stored.
+#pragma unroll
+        for (int i = 0; i < S::B_PER_THREAD; ++i) {
+            const int slot = slot0 + i * 64 + lane;
+            const int row = slot / S::B_CPR, c = (slot % S::B_CPR) ^ ((row & 3) << 1);
+            b_off[i] = (row * p.N + n0 + c * 8) * 2;
+            b_col[i] = n0 + c * 8;
+        }
 #pragma unroll
         for (int a = 0; a < S::MTW; ++a)
 #pragma unroll
@@ -143,53 +243,111 @@ struct TileKernel {
     }
 
     // ---- global -> registers -------------------------------------------------------------
-    // Raw BFP16 of A rows [row0, row0 + T_MA), k in [k0, k0 + T_K) into register set `set`.
-    // Rows >= M fall off the end of the planes (zero mantissas); chunks with k >= ldm are sent out
-    // of range explicitly; mantissa bytes between K and ldm are zero by the layout's contract.
-    template <int set = S::PF - 1>
-    ATB_DEV void load_a(int row0, int k0)
+    // Descriptors are wave-uniform by construction; saying so keeps them in scalar registers.
+    template <class T>
+    ATB_DEV __amdgpu_buffer_rsrc_t make_rsrc(const T *ptr, int bytes)
     {
-#pragma unroll
-        for (int i = 0; i < S::A_PER_THREAD; ++i) {
-            const int grow = row0 + a_row + i * (S::NT / S::A_CPR);
-            const int k = k0 + a_q * S::ACE;
-            const bool in = k < p.ldm;
-            const int moff = in ? grow * p.ldm + k : kOutOfRange;
-            const int eoff = in ? grow * p.lde + (k >> 3) : kOutOfRange;
-            if constexpr (S::ACE == 16) {
-                a_mant[set][i] = __builtin_amdgcn_raw_buffer_load_b128(rs.am, moff, 0, 0);
-                a_expo[set][i] = __builtin_amdgcn_raw_buffer_load_b16(rs.ae, eoff, 0, 0);
-            } else {
-                intx2 t = __builtin_amdgcn_raw_buffer_load_b64(rs.am, moff, 0, 0);
-                a_mant[set][i] = intx4{t.x, t.y, 0, 0};
-                a_expo[set][i] = __builtin_amdgcn_raw_buffer_load_b8(rs.ae, eoff, 0, 0);
-            }
+        const uint64_t a = reinterpret_cast<uint64_t>(ptr);
+        const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a);
+        const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+        void *u = reinterpret_cast<void *>(((uint64_t)hi << 32) | lo);
+        return __builtin_amdgcn_make_buffer_rsrc(u, 0, __builtin_amdgcn_readfirstlane(bytes), kRsrcFlags);
+    }
+
+    ATB_DEV void remake_a()
+    {
+        rs.am = make_rsrc(am_ptr, am_left);
+        rs.ae = make_rsrc(ae_ptr, ae_left);
+    }
+
+    ATB_DEV void remake_b() { rs.b = make_rsrc(b_ptr, b_left); }
+
+    // Chunk i of sub-tile `sub` of the K-step the A descriptors point at, into register set `set`.
+    // After the last chunk of the last sub-tile the descriptors move on to the next K-step.
+    template <int set, int sub, int i>
+    ATB_DEV void load_a_chunk()
+    {
+        if constexpr (S::ACE == 16) {
+            a_mant[set][i] = __builtin_amdgcn_raw_buffer_load_b128(rs.am, a_moff[sub][i], 0, 0);
+        } else {
+            intx2 t = __builtin_amdgcn_raw_buffer_load_b64(rs.am, a_moff[sub][i], 0, 0);
+            a_mant[set][i] = intx4{t.x, t.y, 0, 0};
+        }
+        // the aligned dword that holds this chunk's exponent byte(s): sub-dword loads are far slower
+        a_expo[set][i] = __builtin_amdgcn_raw_buffer_load_b32(rs.ae, a_eoff[sub][i], 0, 0);
+        if constexpr (sub == S::RHO - 1 && i == S::A_PER_THREAD - 1 && !(ATB_ABLATE & 128)) {
+            am_ptr += S::T_K;
+            ae_ptr += S::T_K / 8;
+            am_left = max(am_left - S::T_K, 0);
+            ae_left = max(ae_left - S::T_K / 8, 0);
+            remake_a();
         }
     }
 
-    // B rows [k0, k0 + T_K), columns [n0, n0 + T_N), 8 columns per chunk.
-    // VEC (N % 8 == 0): one 16-byte load per chunk; rows >= K fall off the end of B (zero); columns
-    // >= N wrap into the next row, which only feeds output columns that are never stored.
-    // !VEC: element loads, each masked.
-    ATB_DEV void load_b(int k0)
+    template <int set, int sub, int i = 0>
+    ATB_DEV void load_a()
     {
-#pragma unroll
-        for (int i = 0; i < S::B_PER_THREAD; ++i) {
-            const int k = k0 + b_row + i * (S::NT / S::B_CPR);
-            const int n = n0 + b_c * 8;
-            if constexpr (VEC) {
-                b_raw[i] = __builtin_amdgcn_raw_buffer_load_b128(rs.b, (k * p.N + n) * 2, 0, 0);
-            } else {
-                unsigned t[8];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int off = (n + j < p.N) ? (k * p.N + n + j) * 2 : kOutOfRange;
-                    t[j] = __builtin_amdgcn_raw_buffer_load_b16(rs.b, off, 0, 0);
-                }
-                b_raw[i] = intx4{(int)(t[0] | (t[1] << 16)), (int)(t[2] | (t[3] << 16)),
-                                 (int)(t[4] | (t[5] << 16)), (int)(t[6] | (t[7] << 16))};
-            }
+        if constexpr (i < S::A_PER_THREAD) {
+            load_a_chunk<set, sub, i>();
+            load_a<set, sub, i + 1>();
         }
+    }
+
+    // Request i of the next B tile in fetch order, destined for LDS buffer `buf`.
+    // VEC (N % 8 == 0): one 16-byte load per lane straight into LDS (no registers, no ds_write);
+    // completion is awaited with wait_b_landed() before the barrier that publishes the tile.
+    // !VEC: element loads into registers, each masked against N; store_b_chunk() writes them later.
+    template <int i>
+    ATB_DEV void load_b_chunk(int buf)
+    {
+        if constexpr (VEC) {
+#if defined(__HIP_DEVICE_COMPILE__)
+            typedef __attribute__((address_space(3))) void lds_void;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs.b, (lds_void *)(b_req[buf] + i * 1024), 16, b_off[i], 0, 0, 0);
+#else
+            (void)buf;   // the host pass only parses this function
+#endif
+        } else {
+            const int n = b_col[i];
+            unsigned t[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                t[j] = __builtin_amdgcn_raw_buffer_load_b16(rs.b, (n + j < p.N) ? b_off[i] + 2 * j : kOutOfRange, 0, 0);
+            b_raw[i] = intx4{(int)(t[0] | (t[1] << 16)), (int)(t[2] | (t[3] << 16)),
+                             (int)(t[4] | (t[5] << 16)), (int)(t[6] | (t[7] << 16))};
+        }
+        if constexpr (i == S::B_PER_THREAD - 1 && !(ATB_ABLATE & 128)) {
+            b_ptr += S::T_K * p.N;
+            b_left = max(b_left - S::T_K * p.N * 2, 0);
+            remake_b();
+        }
+    }
+
+    template <int i = 0>
+    ATB_DEV void load_b(int buf)
+    {
+        if constexpr (i < S::B_PER_THREAD) {
+            load_b_chunk<i>(buf);
+            load_b<i + 1>(buf);
+        }
+    }
+
+    // Workgroup barrier between microkernels.  It publishes this wave's LDS stores (lgkmcnt) but,
+    // unlike __syncthreads(), does not wait for memory requests in flight: the A sub-tiles being
+    // fetched into registers and the B tile being fetched straight into the other LDS buffer stay
+    // in flight across it (the B tile is awaited explicitly where it has to be complete).
+    ATB_DEV void switch_barrier()
+    {
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    }
+
+    // Block until this lane's memory requests, except the `younger` most recent ones, have
+    // completed (s_waitcnt vmcnt; requests complete in order).
+    template <int younger>
+    ATB_DEV void wait_vm()
+    {
+        static_assert(younger >= 0 && younger < 64, "vmcnt is a 6-bit counter");
+        __builtin_amdgcn_s_waitcnt((younger & 15) | (7 << 4) | (15 << 8) | ((younger >> 4) << 14));
     }
 
     // ---- registers -> LDS ----------------------------------------------------------------
@@ -199,23 +357,33 @@ struct TileKernel {
     template <int set, int i, int t>
     ATB_DEV void decode_pair(char *a_dst)
     {
-        if constexpr (t % 4 == 0) shift = (int)((a_expo[set][i] >> (8 * (t / 4))) & 0xFFu) - 133;
+        if constexpr (t % 4 == 0) shift = (int)((a_expo[set][i] >> (e_shift + 8 * (t / 4))) & 0xFFu) - 133;
         const int w = a_mant[set][i][t / 2];
-        const float f0 = ldexpf(mant_to_float(w, (t % 2) * 2), shift);
-        const float f1 = ldexpf(mant_to_float(w, (t % 2) * 2 + 1), shift);
-        union { bf16x2 v; unsigned u; } pk;
-        pk.v = bf16x2{(__bf16)f0, (__bf16)f1};
-        dec[t % 4] = pk.u;
+        if constexpr (ATB_ABLATE & 1) {
+            dec[t % 4] = (unsigned)w + (unsigned)shift;
+        } else {
+            const float f0 = ldexpf(mant_to_float(w, (t % 2) * 2), shift);
+            const float f1 = ldexpf(mant_to_float(w, (t % 2) * 2 + 1), shift);
+            union { bf16x2 v; unsigned u; } pk;
+            pk.v = bf16x2{(__bf16)f0, (__bf16)f1};
+            dec[t % 4] = pk.u;
+        }
         if constexpr (t % 4 == 3) {
-            char *dst = a_dst + (a_row + i * (S::NT / S::A_CPR)) * S::PA + a_q * (S::ACE * 2) + (t / 4) * 16;
-            *reinterpret_cast<intx4 *>(dst) = intx4{(int)dec[0], (int)dec[1], (int)dec[2], (int)dec[3]};
+            char *dst = a_dst + i * (S::NT / S::A_CPR) * S::PA + (t / 4) * 16;
+            if constexpr (ATB_ABLATE & 8)
+                asm volatile("" ::"v"(dec[0]), "v"(dec[1]), "v"(dec[2]), "v"(dec[3]));
+            else
+                *reinterpret_cast<intx4 *>(dst) = intx4{(int)dec[0], (int)dec[1], (int)dec[2], (int)dec[3]};
         }
     }
 
     template <int i>
     ATB_DEV void store_b_chunk(char *b_dst)
     {
-        *reinterpret_cast<intx4 *>(b_dst + (b_row + i * (S::NT / S::B_CPR)) * S::PB + b_c * 16) = b_raw[i];
+        if constexpr (ATB_ABLATE & 8)
+            asm volatile("" ::"v"(b_raw[i]));
+        else
+            *reinterpret_cast<intx4 *>(b_dst + i * 1024) = b_raw[i];
     }
 
     template <int set, int j = 0>
@@ -237,78 +405,33 @@ struct TileKernel {
     }
 
     // ---- LDS -> registers ----------------------------------------------------------------
-    // The wave's B fragments for one K-step: bfrag[ks][nt] holds, per lane l, column
-    // (wn*NTW + nt)*32 + l%32 and k = ks*16 + 8*(l/32) .. +7.  B sits row-major ([k][n]) in LDS;
-    // ds_read_b64_tr_b16 transposes on the way out: within each group of 16 lanes, lane i addresses
-    // 4 consecutive columns of row i/4, and lane j receives column j of those 4 rows.
-    ATB_DEV void read_b_frags(const char *b_src)
+    // B fragment (ks, nt): per lane l, column (wn*NTW + nt)*32 + l%32 and k = ks*16 + 8*(l/32) .. +7.
+    template <int ks, int nt>
+    ATB_DEV void read_b_frag(const char *const (&b_src)[2])
     {
-        const int blk = lane >> 4, j = lane & 15;
-        const char *base = b_src + (8 * (blk >> 1) + (j >> 2)) * S::PB +
-                           (wn * S::NTW * 32 + 16 * (blk & 1) + 4 * (j & 3)) * 2;
-#pragma unroll
-        for (int ks = 0; ks < S::KS; ++ks) {
-#pragma unroll
-            for (int nt = 0; nt < S::NTW; ++nt) {
-                const char *src = base + ks * 16 * S::PB + nt * 64;
-                typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
-                union { shortx4 s[2]; bf16x8 b; } u;
-                u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(src));
-                u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(src + 4 * S::PB));
-                bfrag[ks][nt] = u.b;
-            }
+        const char *src = b_src[nt & 1] + ks * 16 * S::PB + (nt >> 1) * 128;
+        typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
+        union { shortx4 s[2]; bf16x8 b; } u;
+        u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(src));
+        u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(src + 4 * S::PB));
+        bfrag[ks][nt] = u.b;
+    }
+
+    template <int f = 0>
+    ATB_DEV void read_b_frags_all(const char *const (&b_src)[2])
+    {
+        if constexpr (f < S::KS * S::NTW) {
+            read_b_frag<f / S::NTW, f % S::NTW>(b_src);
+            read_b_frags_all<f + 1>(b_src);
         }
     }
 
-    // A fragment (band il of the sub-tile, k-slice ks): lane l reads row l%32, k = ks*16 + 8*(l/32) .. +7.
-    // Bands of the C tile are dealt round-robin to the wave rows: band il*WM + wm of the sub-tile.
+    // A fragment (band il of the sub-tile, k-slice ks).  Bands of the C tile are dealt round-robin
+    // to the wave rows: this wave reads band il*WM + wm of the sub-tile.
     template <int il, int ks>
     ATB_DEV void read_a_frag(const char *a_src)
     {
-        const char *src = a_src + ((il * S::WM + wm) * 32 + (lane & 31)) * S::PA + (lane >> 5) * 16 + ks * 32;
-        afrag[il % 2][ks] = *reinterpret_cast<const bf16x8 *>(src);
-    }
-
-    // ---- one microkernel, software-pipelined by hand ---------------------------------------
-    // Side work j of phase s: decode + LDS write of the next A sub-tile, then (last phase of the
-    // K-step) the LDS writes of the next B tile.
-    template <int s, int j>
-    ATB_DEV void side(char *a_dst, char *b_dst)
-    {
-        if constexpr (j < S::NPAIR) {
-            decode_pair<0, j / (S::ACE / 2), j % (S::ACE / 2)>(a_dst);
-        } else {
-            store_b_chunk<j - S::NPAIR>(b_dst);
-        }
-    }
-
-    template <int s, int j, int jend>
-    ATB_DEV void side_range(char *a_dst, char *b_dst)
-    {
-        if constexpr (j < jend) {
-            side<s, j>(a_dst, b_dst);
-            side_range<s, j + 1, jend>(a_dst, b_dst);
-        }
-    }
-
-    // Slot m: one MFMA, then its share of the side work and (after the last column band of a
-    // k-slice) the A fragment of the same k-slice of the next band.  The fences pin this order, so
-    // the VALU decode and the LDS traffic issue in the shadow of the 8-pass MFMA.
-    template <int s, int m>
-    ATB_DEV void slots(const char *a_src, char *a_dst, char *b_dst)
-    {
-        if constexpr (m < S::NM) {
-            constexpr int il = m / (S::KS * S::NTW), ks = (m / S::NTW) % S::KS, nt = m % S::NTW;
-            constexpr int local = (s * S::SMT) / S::WM + il;      // accumulator band of this wave
-            constexpr int nside = S::NPAIR + ((s + 1 == S::RHO) ? S::B_PER_THREAD : 0);
-            acc[local][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag[ks][nt], afrag[il % 2][ks],
-                                                                    acc[local][nt], 0, 0, 0);
-            ATB_FENCE();
-            side_range<s, (m * nside) / S::NM, ((m + 1) * nside) / S::NM>(a_dst, b_dst);
-            if constexpr (nt == S::NTW - 1 && il + 1 < S::PER) read_a_frag<il + 1, ks>(a_src);
-            ATB_FENCE();
-            slots<s, m + 1>(a_src, a_dst, b_dst);
-        }
+        afrag[il % 2][ks] = *reinterpret_cast<const bf16x8 *>(a_src + il * S::WM * 32 * S::PA + ks * 32);
     }
 
     template <int ks = 0>
@@ -320,43 +443,92 @@ struct TileKernel {
         }
     }
 
-    // The raw A sub-tiles in flight form a queue of PF register sets: set 0 is decoded next, a new
-    // fetch goes into set PF-1.
-    ATB_DEV void shift_a_queue()
+    // ---- one microkernel, software-pipelined by hand ---------------------------------------
+    // Side work of phase (kpar, s), in issue order: the memory requests for A sub-tile g+PF (and, in
+    // the first phase of a K-step, for the B tile two K-steps ahead), the decode + LDS write of A
+    // sub-tile g+1, and (last phase of the K-step) the LDS writes of the B tile fetched in the first.
+    template <int s>
+    static constexpr int n_side()
     {
-#pragma unroll
-        for (int q = 0; q + 1 < S::PF; ++q)
-#pragma unroll
-            for (int i = 0; i < S::A_PER_THREAD; ++i) {
-                a_mant[q][i] = a_mant[q + 1][i];
-                a_expo[q][i] = a_expo[q + 1][i];
-            }
+        return S::A_PER_THREAD + (s == 0 ? S::B_PER_THREAD : 0) + S::NPAIR + ((!VEC && s + 1 == S::RHO) ? S::B_PER_THREAD : 0);
     }
 
-    // Phase s of K-step kt: microkernel on sub-tile s, while sub-tile s+1 is decoded into the other
-    // LDS buffer and sub-tile s+PF is fetched from memory.  Sub-tile g = kt*RHO + s sits in LDS
-    // buffer g % 2.
-    template <int s>
-    ATB_DEV void phases(int kt)
+    template <int kpar, int s, int j>
+    ATB_DEV void side()
+    {
+        constexpr int g = kpar * S::RHO + s;
+        constexpr int n_la = S::A_PER_THREAD, n_lb = (s == 0 ? S::B_PER_THREAD : 0);
+        if constexpr (ATB_ABLATE & 4) {
+            if constexpr (j >= n_la + n_lb) {
+                if constexpr (j < n_la + n_lb + S::NPAIR)
+                    decode_pair<(g + 1) % S::PF, (j - n_la - n_lb) / (S::ACE / 2), (j - n_la - n_lb) % (S::ACE / 2)>(a_wr[(g + 1) % 2]);
+                else
+                    store_b_chunk<j - n_la - n_lb - S::NPAIR>(b_wr[kpar]);
+            }
+        } else if constexpr (j < n_la) {
+            if constexpr (!(ATB_ABLATE & 256)) load_a_chunk<g % S::PF, (s + S::PF) % S::RHO, j>();
+        } else if constexpr (j < n_la + n_lb) {
+            if constexpr (!(ATB_ABLATE & 512)) load_b_chunk<j - n_la>(kpar);
+        } else if constexpr (j < n_la + n_lb + S::NPAIR) {
+            decode_pair<(g + 1) % S::PF, (j - n_la - n_lb) / (S::ACE / 2), (j - n_la - n_lb) % (S::ACE / 2)>(a_wr[(g + 1) % 2]);
+        } else {
+            store_b_chunk<j - n_la - n_lb - S::NPAIR>(b_wr[kpar]);
+        }
+    }
+
+    template <int kpar, int s, int j, int jend>
+    ATB_DEV void side_range()
+    {
+        if constexpr (j < jend) {
+            side<kpar, s, j>();
+            side_range<kpar, s, j + 1, jend>();
+        }
+    }
+
+    // Slot m: one MFMA, then its share of the side work; after the last column band of a k-slice
+    // the A fragment of the same k-slice of the next band; in the last band of the K-step the B
+    // fragment just used is replaced by the next K-step's.  The fences pin this order, so that the
+    // VALU decode and the LDS traffic issue in the shadow of the 8-pass MFMA.
+    template <int kpar, int s, int m>
+    ATB_DEV void slots()
+    {
+        if constexpr (m < S::NM) {
+            constexpr int il = m / (S::KS * S::NTW), ks = (m / S::NTW) % S::KS, nt = m % S::NTW;
+            constexpr int local = (s * S::SMT) / S::WM + il;      // accumulator band of this wave
+            constexpr bool last_phase = (s + 1 == S::RHO);
+            constexpr int nside = n_side<s>();
+            constexpr int g = kpar * S::RHO + s;
+            if constexpr (!(ATB_ABLATE & 32))
+                acc[local][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag[ks][nt], afrag[il % 2][ks],
+                                                                        acc[local][nt], 0, 0, 0);
+            else
+                acc[local][nt][0] += (float)bfrag[ks][nt][0] + (float)afrag[il % 2][ks][0];
+            ATB_FENCE();
+            side_range<kpar, s, (m * nside) / S::NM, ((m + 1) * nside) / S::NM>();
+            if constexpr (nt == S::NTW - 1 && il + 1 < S::PER && !(ATB_ABLATE & 16)) read_a_frag<il + 1, ks>(a_rd[g % 2]);
+            if constexpr (last_phase && il + 1 == S::PER && !(ATB_ABLATE & 2)) read_b_frag<ks, nt>(b_rd[kpar ^ 1]);
+            ATB_FENCE();
+            slots<kpar, s, m + 1>();
+        }
+    }
+
+    // Phase s of a K-step of parity kpar.
+    template <int kpar, int s>
+    ATB_DEV void phases()
     {
         if constexpr (s < S::RHO) {
-            const int k0 = kt * S::T_K;
-            const int cur = (S::RHO % 2 == 0) ? (s & 1) : ((kt + s) & 1);
-            {
-                constexpr int sf = (s + S::PF) % S::RHO, kf = (s + S::PF) / S::RHO;
-                load_a(m0 + sf * S::T_MA, k0 + kf * S::T_K);
-            }
-            if constexpr (s == 0) load_b(k0 + S::T_K);
-            ATB_FENCE();                 // keep the memory requests ahead of everything else
-            const char *a_src = cur ? a_lds[1] : a_lds[0];
-            char *a_dst = cur ? a_lds[0] : a_lds[1];
-            char *b_dst = (kt & 1) ? b_lds[0] : b_lds[1];
-            read_first_band(a_src);
+            constexpr int g = kpar * S::RHO + s;
+            read_first_band(a_rd[g % 2]);
             ATB_FENCE();
-            slots<s, 0>(a_src, a_dst, b_dst);
-            shift_a_queue();
-            __syncthreads();             // the "kernel switch" of the ATB nest
-            phases<s + 1>(kt);
+            ATB_STAMP(1);
+            slots<kpar, s, 0>();
+            ATB_STAMP(2);
+            // the B tile requested in the first phase must have landed in LDS before the barrier
+            // that ends the K-step; only the A requests of the later phases are younger
+            if constexpr (VEC && s + 1 == S::RHO) wait_vm<(S::RHO - 1) * S::A_PER_THREAD * 2>();
+            if constexpr (!(ATB_ABLATE & 64)) switch_barrier();   // the "kernel switch" of the ATB nest
+            ATB_STAMP(3);
+            phases<kpar, s + 1>();
         }
     }
 
@@ -364,26 +536,33 @@ struct TileKernel {
     ATB_DEV void prologue_loads()
     {
         if constexpr (g < S::PF) {
-            load_a<g>(m0 + (g % S::RHO) * S::T_MA, (g / S::RHO) * S::T_K);
+            load_a<g, g % S::RHO>();
             prologue_loads<g + 1>();
         }
     }
 
     ATB_DEV void run()
     {
-        // prologue: first B tile, the first PF A sub-tiles into registers, sub-tile 0 into LDS
+        // prologue: B tiles 0 and 1 into LDS, the first PF A sub-tiles into registers, sub-tile 0
+        // into LDS, B tile 0 into fragment registers
         load_b(0);
         prologue_loads();
-        store_b_all(b_lds[0]);
-        store_a_all<0>(a_lds[0]);
-        shift_a_queue();
+        if constexpr (!VEC) store_b_all(b_wr[0]);
+        load_b(1);
+        store_a_all<0>(a_wr[0]);
+        if constexpr (VEC) wait_vm<0>(); else store_b_all(b_wr[1]);
         __syncthreads();
+        read_b_frags_all(b_rd[0]);
 
+        // an odd number of K-steps is rounded up: the extra step multiplies by B rows >= K, which
+        // read as zero
         const int KT = (p.K + S::T_K - 1) / S::T_K;
-        for (int kt = 0; kt < KT; ++kt) {
-            read_b_frags((kt & 1) ? b_lds[1] : b_lds[0]);
-            phases<0>(kt);
+        ATB_STAMP(0);
+        for (int kt = 0; kt < KT; kt += 2) {
+            phases<0, 0>();
+            phases<1, 0>();
         }
+        ATB_TRACE_FLUSH();
         store_c();
     }
 
@@ -479,7 +658,7 @@ const Instance g_instances[] = {
     make_instance<Shape<64, 256, 64, 256, 2, 2, 2>>(),
     make_instance<Shape<32, 256, 64, 256, 1, 4, 4>>(),
     // small tiles for small problems
-    make_instance<Shape<64, 64, 64, 64, 2, 2, 1>>(),
+    make_instance<Shape<64, 64, 64, 64, 2, 2, 2>>(),
     make_instance<Shape<32, 64, 64, 64, 1, 2, 2>>(),
 };
 
