@@ -34,7 +34,61 @@ def parse_args():
     ap.add_argument("--no-sweep", action="store_true", help="skip the per-instance sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-rows", type=int, default=1024, help="rows of C the oracle computes for the CPU baseline")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run a plain device-to-device copy of known size instead (reference for the HBM byte counters)")
     return ap.parse_args()
+
+
+def copy_probe():
+    """A plain copy kernel of known size: 10 x (read 1 GiB + write 1 GiB).  Run under
+    `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` to find what the counters read per byte moved."""
+    import torch
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda")
+    src.fill_(3)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(10):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"copy_probe": True, "bytes_read_per_copy": n, "bytes_written_per_copy": n, "copies": 10}), flush=True)
+
+
+def spearman(a, b):
+    """Rank correlation of two equally long sequences (no tie correction needed at this size)."""
+    def ranks(x):
+        order = sorted(range(len(x)), key=lambda i: x[i])
+        r = [0.0] * len(x)
+        i = 0
+        while i < len(order):
+            j = i
+            while j + 1 < len(order) and x[order[j + 1]] == x[order[i]]:
+                j += 1
+            for k in range(i, j + 1):
+                r[order[k]] = (i + j) / 2.0
+            i = j + 1
+        return r
+    ra, rb = ranks(a), ranks(b)
+    n = len(a)
+    ma, mb = sum(ra) / n, sum(rb) / n
+    cov = sum((x - ma) * (y - mb) for x, y in zip(ra, rb))
+    va = sum((x - ma) ** 2 for x in ra) ** 0.5
+    vb = sum((y - mb) ** 2 for y in rb) ** 0.5
+    return cov / (va * vb) if va > 0 and vb > 0 else 0.0
+
+
+def hbm_traffic(workload, tiles):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one for this
+    workload and these tile factors (the counters cannot be read from inside this process)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if not os.path.exists(path):
+        return None
+    try:
+        table = json.load(open(path))
+    except Exception:
+        return None
+    key = f"{workload}:{','.join(str(t) for t in tiles)}"
+    return table.get(key, {}).get("bytes_per_launch")
 
 
 def time_plan(plan, A_bfp, B, C, steps, warmup):
@@ -57,6 +111,9 @@ def time_plan(plan, A_bfp, B, C, steps, warmup):
 
 def main():
     args = parse_args()
+    if args.copy_probe:
+        copy_probe()
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); nothing is sharded across GPUs.", file=sys.stderr)
         sys.exit(2)
@@ -131,7 +188,8 @@ def main():
                    "accumulate": "fp32", "out": "bf16"},
         "pct_of_bf16_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": {"bound": "mfma", "achieved": round(kernel_tflops, 2), "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(kernel_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "unit": "TFLOP/s", "frac": round(kernel_tflops / PEAK_BF16_TFLOPS, 4),
+                     "traffic": hbm_traffic(args.workload, tiles),
                      "kernel": "atb_gemm_kernel", "kernel_ms": round(kernel_ms, 4),
                      "algorithmic_flop_per_launch": flop},
     }
@@ -139,6 +197,10 @@ def main():
         out["rho_sweep"] = sweep
         if sym and best_atb:
             out["atb_vs_symmetric"] = round(best_atb["tflops"] / sym[0]["tflops"], 4)
+        fam = [s for s in sweep if s["tiles"][1:] == list(tiles[1:])]
+        if len(fam) >= 3:
+            out["model_vs_measured_rank_spearman"] = round(spearman([s["model_tflops"] for s in fam],
+                                                                    [s["tflops"] for s in fam]), 3)
 
     if not args.no_cpu:
         import oracle

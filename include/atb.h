@@ -134,6 +134,8 @@ typedef struct atb_hw_params {
     double acc_bytes;         /* MI355X only: accumulator-register bytes per core; 0 = C lives in `buffer_bytes` */
     double clock_hz;
     double delta_cycles;      /* delta: cost of one microkernel switch (Sec. 5) */
+    double fill_cycles;       /* MI355X extension, 0 on XDNA2: pipeline-fill cost per K-step that an A sub-tile of
+                                 T_MC rows exposes; a sub-tile of T_MC/rho rows exposes fill_cycles/rho (see atb_model_eval) */
     double eta, eps, II;      /* Eff_micro(T_K) = eta T_K / (eps + eta II T_K), Eq. (12) */
     double a_bytes, b_bytes, c_bytes; /* bytes per element of A, B, C moved from off-chip */
     double a_buf_bytes, b_buf_bytes;  /* bytes per element of A, B as buffered (Eq. 1); 0 = same as above */
@@ -161,7 +163,9 @@ typedef struct atb_choice {
 } atb_choice;
 
 /* Evaluate the model (Eqs. 1, 2, 11, 12, 15) for one set of tile factors.
- * hw == NULL means MI355X.  Pure host arithmetic. */
+ * hw == NULL means MI355X.  Pure host arithmetic.  Per output tile and K-step
+ * the time is  2 T_MC T_N T_K / (Peak_core Eff_micro) + delta rho + fill / rho  (Eq. 14 plus the
+ * fill term; with fill_cycles = 0 this is the paper's Eq. 14 / Eq. 15 exactly). */
 atb_status atb_model_eval(int64_t M, int64_t N, int64_t K, int T_MA, int T_MC, int T_K, int T_N,
                           const atb_hw_params *hw, atb_choice *out);
 

@@ -30,7 +30,7 @@ class HwParams(ctypes.Structure):
                 ("array_rows", ctypes.c_int), ("array_cols", ctypes.c_int),
                 ("bw_offchip", ctypes.c_double), ("buffer_bytes", ctypes.c_double),
                 ("acc_bytes", ctypes.c_double), ("clock_hz", ctypes.c_double),
-                ("delta_cycles", ctypes.c_double), ("eta", ctypes.c_double),
+                ("delta_cycles", ctypes.c_double), ("fill_cycles", ctypes.c_double), ("eta", ctypes.c_double),
                 ("eps", ctypes.c_double), ("II", ctypes.c_double),
                 ("a_bytes", ctypes.c_double), ("b_bytes", ctypes.c_double), ("c_bytes", ctypes.c_double),
                 ("a_buf_bytes", ctypes.c_double), ("b_buf_bytes", ctypes.c_double),

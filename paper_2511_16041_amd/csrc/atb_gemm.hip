@@ -69,7 +69,13 @@ struct Shape {
     static constexpr int NPAIR = A_PER_THREAD * ACE / 2;   // pairs of mantissas each thread decodes per sub-tile
     static constexpr int B_CHUNKS = T_K * (T_N / 8);
     static constexpr int B_PER_THREAD = B_CHUNKS / NT;
-    static constexpr int B_CPR = T_N / 8;         // chunks per B row
+    static constexpr int B_CPR = T_N / 8;         // 16-byte chunks per B row
+    // B swizzle: chunk c of row k sits at chunk position c ^ ((k & 3) << SWZ) of its row.  A
+    // transposing read touches, per 32 lanes, 4 rows x 2 neighbouring 32-byte pieces; with SWZ = 2
+    // these 8 pieces cover 256 consecutive bytes, i.e. every LDS bank once.  Narrow tiles (fewer than
+    // 16 chunks per row) can only afford SWZ = 1, which keeps 16 lanes conflict-free.
+    static constexpr int SWZ = (T_N / 8 >= 16) ? 2 : 1;
+    static constexpr int NBASE = (NTW < 4) ? NTW : 4;   // distinct per-lane read bases (the swizzle permutes 4 bands)
     static_assert(T_MC % T_MA == 0, "rho must be an integer");
     static_assert(PF >= 2 && (2 * RHO) % PF == 0, "prefetch distance: at least 2 (fetch and decode overlap), dividing two K-steps of sub-tiles");
     static_assert(128 % T_K == 0 && T_K % 32 == 0, "T_K must divide the 128-byte row padding of the mantissa plane; exponent dwords stay aligned");
@@ -148,7 +154,7 @@ struct TileKernel {
     int tid, lane, wm, wn, m0, n0;
     // LDS byte addresses of this thread's staging writes and fragment reads, per buffer
     char *a_wr[2], *b_wr[2];
-    const char *a_rd[2], *b_rd[2][2];  // b_rd[buffer][parity of the column band]
+    const char *a_rd[2], *b_rd[2][S::NBASE];  // b_rd[buffer][column band mod 4]
     char *b_req[2];                    // LDS byte address of this wave's first 1 KiB B request, per buffer
     // Byte offsets of this thread's global loads relative to the current K-step.  They never
     // change: the K-step advance is applied to the (scalar) buffer descriptors instead, base up and
@@ -183,8 +189,8 @@ struct TileKernel {
         e_shift = ((a_q * (S::ACE / 8)) & 3) * 8;
         // B staging.  The tile is row-major in LDS ([k][n], no padding).  The wave's request i fills
         // the 1 KiB of the tile that starts at (wave*B_PER_THREAD + i) KiB, lane l the 16-byte slot
-        // l of it.  Chunk c of row k is stored at chunk position c ^ ((k & 3) << 1) of its row, so
-        // that the four rows a transposing read touches fall into different banks.
+        // l of it.  Chunk c of row k is stored at chunk position c ^ ((k & 3) << SWZ) of its row, so
+        // that the rows a transposing read touches fall into different banks.
         const int slot0 = __builtin_amdgcn_readfirstlane(wave) * S::B_PER_THREAD * 64;
         const int blk = lane >> 4, j = lane & 15, r = j >> 2;
 #pragma unroll
@@ -198,12 +204,12 @@ struct TileKernel {
             a_rd[b] = a_base + (wm * 32 + (lane & 31)) * S::PA + (lane >> 5) * 16;
             // B fragment through ds_read_b64_tr_b16: within each group of 16 lanes, lane i addresses
             // 4 consecutive columns of row i/4 (8 bytes, half a chunk), and lane j receives column j
-            // of those 4 rows.  For rows 2, 3 (mod 4) the swizzle flips bit 2 of the chunk index,
-            // which is the parity of the 32-column band: one base address per parity.
+            // of those 4 rows.  The swizzle of row r (mod 4) permutes the chunk index, so each of the
+            // first NBASE column bands gets its own per-lane base; band nt >= 4 adds (nt / 4) * 256 bytes.
 #pragma unroll
-            for (int e = 0; e < 2; ++e) {
+            for (int e = 0; e < S::NBASE; ++e) {
                 const int chunk = 4 * (wn * S::NTW + e) + 2 * (blk & 1) + ((j & 3) >> 1);
-                b_rd[b][e] = b_base + (8 * (blk >> 1) + r) * S::PB + ((chunk ^ (r << 1)) * 16) + (j & 1) * 8;
+                b_rd[b][e] = b_base + (8 * (blk >> 1) + r) * S::PB + ((chunk ^ (r << S::SWZ)) * 16) + (j & 1) * 8;
             }
         }
         am_ptr = p.Am;
@@ -230,7 +236,7 @@ struct TileKernel {
 #pragma unroll
         for (int i = 0; i < S::B_PER_THREAD; ++i) {
             const int slot = slot0 + i * 64 + lane;
-            const int row = slot / S::B_CPR, c = (slot % S::B_CPR) ^ ((row & 3) << 1);
+            const int row = slot / S::B_CPR, c = (slot % S::B_CPR) ^ ((row & 3) << S::SWZ);
             b_off[i] = (row * p.N + n0 + c * 8) * 2;
             b_col[i] = n0 + c * 8;
         }
@@ -407,9 +413,9 @@ struct TileKernel {
     // ---- LDS -> registers ----------------------------------------------------------------
     // B fragment (ks, nt): per lane l, column (wn*NTW + nt)*32 + l%32 and k = ks*16 + 8*(l/32) .. +7.
     template <int ks, int nt>
-    ATB_DEV void read_b_frag(const char *const (&b_src)[2])
+    ATB_DEV void read_b_frag(const char *const (&b_src)[S::NBASE])
     {
-        const char *src = b_src[nt & 1] + ks * 16 * S::PB + (nt >> 1) * 128;
+        const char *src = b_src[nt % S::NBASE] + ks * 16 * S::PB + (nt / S::NBASE) * (S::NBASE * 64);
         typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
         union { shortx4 s[2]; bf16x8 b; } u;
         u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(src));
@@ -418,7 +424,7 @@ struct TileKernel {
     }
 
     template <int f = 0>
-    ATB_DEV void read_b_frags_all(const char *const (&b_src)[2])
+    ATB_DEV void read_b_frags_all(const char *const (&b_src)[S::NBASE])
     {
         if constexpr (f < S::KS * S::NTW) {
             read_b_frag<f / S::NTW, f % S::NTW>(b_src);

@@ -6,6 +6,7 @@
 //   AI_array = 2 / (a/(cols T_N) + b/(rows T_MC) + c/K)                    Eq. (2)
 //   Eff_micro(T_K) = eta T_K / (eps + eta II T_K)                          Eq. (12)
 //   Eff_core = 1 / (1/Eff_micro + delta rho Peak_core / (2 T_MC T_N T_K))  Eq. (15)
+//              (MI355X: delta rho + fill/rho in place of delta rho, see atb_hw_params.fill_cycles)
 //   Perf     = min(AI_array BW, Eff_core Peak_core N_core)                 Eq. (11)
 //
 // On MI355X the C tile lives in accumulator registers, so Eq. (1) splits in
@@ -34,6 +35,7 @@ extern "C" void atb_hw_params_xdna2(atb_hw_params *hw)
     hw->buffer_bytes = 63.0 * 1024.0;            // Sec. 3.2
     hw->acc_bytes = 0.0;                         // C is buffered in L1
     hw->delta_cycles = 50.0;                     // Sec. 5
+    hw->fill_cycles = 0.0;
     hw->eta = 0.03;                              // fitted to Table 1's Eff_micro column
     hw->eps = 1.0;
     hw->II = 1.2;
@@ -57,10 +59,14 @@ extern "C" void atb_hw_params_mi355x(atb_hw_params *hw)
     hw->bw_offchip = 8.0e12;                     // HBM3E
     hw->buffer_bytes = 160.0 * 1024.0;           // LDS per CU
     hw->acc_bytes = 256.0 * 1024.0;              // 4 waves x 256 accumulator VGPRs x 64 lanes x 4 B
-    hw->delta_cycles = 300.0;                    // one workgroup barrier + pipeline drain per sub-tile (measured)
-    hw->eta = 0.05;
+    // Fitted to the measured K-step times of the 256x256x64 instances at rho = 1, 2, 4, 8 on 8192^3
+    // (in cycles of the nominal 2.4 GHz clock): 3983 + 109 rho + 909 / rho, against 2048 cycles of
+    // MFMA issue, i.e. Eff_micro(64) = 0.514.
+    hw->delta_cycles = 109.0;
+    hw->fill_cycles = 909.0;
+    hw->eta = 0.0287;
     hw->eps = 1.0;
-    hw->II = 1.3;
+    hw->II = 1.4;
     hw->a_bytes = 1.125;                         // A BFP16: 9 bytes per 8 elements
     hw->b_bytes = 2.0;
     hw->c_bytes = 2.0;
@@ -98,7 +104,9 @@ extern "C" atb_status atb_model_eval(int64_t M, int64_t N, int64_t K, int T_MA, 
     r.feasible = (r.buffer_bytes <= hw.buffer_bytes) && (!c_in_regs || r.acc_bytes <= hw.acc_bytes);
     r.eff_micro = hw.eta * T_K / (hw.eps + hw.eta * hw.II * T_K);
     const double delta_s = hw.delta_cycles / hw.clock_hz;
-    r.eff_core = 1.0 / (1.0 / r.eff_micro + delta_s * rho * hw.peak_core_flops / (2.0 * T_MC * (double)T_N * T_K));
+    const double fill_s = hw.fill_cycles / hw.clock_hz;
+    r.eff_core = 1.0 / (1.0 / r.eff_micro +
+                        (delta_s * rho + fill_s / rho) * hw.peak_core_flops / (2.0 * T_MC * (double)T_N * T_K));
     r.mem_bound = r.ai * hw.bw_offchip;
     r.compute_bound = r.eff_core * hw.peak_core_flops * hw.n_core;
     if (c_in_regs) {

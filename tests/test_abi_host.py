@@ -116,13 +116,23 @@ def test_model_mi355x_mode_and_selector():
     # C lives in registers: the LDS term has no C share
     ab, bb = hw.a_buf_bytes, hw.b_buf_bytes
     assert ch.buffer_bytes == pytest.approx(2 * ab * 64 * 64 + 2 * bb * 64 * 256)
-    # Eq. (15) ordering: at fixed C tile and T_K, larger rho never raises the compute bound
+    # Eq. (15) ordering with the fill term switched off: at fixed C tile and T_K, larger rho lowers
+    # the compute bound; the LDS footprint always shrinks with rho
+    hw0 = atb.hw_params("mi355x")
+    hw0.fill_cycles = 0.0
     prev = None
     for T_MA in (256, 128, 64, 32):
-        c = atb.model_eval(8192, 8192, 8192, T_MA, 256, 64, 256, hw)
+        c = atb.model_eval(8192, 8192, 8192, T_MA, 256, 64, 256, hw0)
         if prev is not None:
             assert c.eff_core < prev.eff_core and c.buffer_bytes < prev.buffer_bytes
         prev = c
+    # with the fill term: T = T_mfma / Eff_micro + delta rho + fill / rho per K-step
+    for T_MA in (256, 128, 64, 32):
+        rho = 256 // T_MA
+        c = atb.model_eval(8192, 8192, 8192, T_MA, 256, 64, 256, hw)
+        t_mfma = 2.0 * 256 * 256 * 64 / hw.peak_core_flops
+        t = t_mfma / c.eff_micro + (hw.delta_cycles * rho + hw.fill_cycles / rho) / hw.clock_hz
+        assert c.eff_core == pytest.approx(t_mfma / t, rel=1e-12)
     ranked = atb.select_tiles(8192, 8192, 8192)
     assert len(ranked) == len(atb.instances())
     assert ranked[0].feasible == 1 and ranked[0].T_MC == 256
