@@ -158,7 +158,7 @@ def main():
             if t[1] != tiles[1] and (M * N) // (t[1] * t[3]) > 65536:
                 continue
             p = atb.Gemm(M, N, K, *t)
-            _, kms = time_plan(p, A_bfp, B, C, max(5, args.steps // 5), 3)
+            _, kms = time_plan(p, A_bfp, B, C, max(5, args.steps // 2), 5)
             p.close()
             sweep.append({"tiles": list(t), "rho": t[1] // t[0], "tflops": round(flop / (kms * 1e-3) / 1e12, 1),
                           "model_tflops": round(pred.get(t, 0.0), 1)})
