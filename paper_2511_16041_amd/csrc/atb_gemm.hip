@@ -42,10 +42,17 @@ typedef short shortx4 __attribute__((ext_vector_type(4)));
 // Sign-extended byte `byte` of word w as float (one v_cvt_f32_i32 with a byte select).
 ATB_DEV float mant_to_float(int w, int byte) { return (float)(int)(signed char)(w >> (8 * byte)); }
 
-template <int T_MA_, int T_MC_, int T_K_, int T_N_, int WM_, int WN_, int PF_>
+template <int T_MA_, int T_MC_, int T_K_, int T_N_, int WM_, int WN_, int PF_, int AB_ = 2>
 struct Shape {
     static constexpr int T_MA = T_MA_, T_MC = T_MC_, T_K = T_K_, T_N = T_N_, WM = WM_, WN = WN_;
     static constexpr int PF = PF_;                // A sub-tiles fetched this many phases ahead of their use
+    // A LDS buffers.  2: sub-tile g+1 is decoded while sub-tile g is multiplied, and each microkernel
+    // starts by reading its first fragments after the switch barrier.  4: the small A sub-tiles of
+    // ATB leave room for a deeper ring: sub-tile g+2 is decoded while g is multiplied, so sub-tile
+    // g+1 is already complete and its first fragments are read before the barrier, which takes the
+    // LDS latency out of every switch.
+    static constexpr int AB = AB_;
+    static constexpr int DA = (AB_ == 4) ? 2 : 1; // decode runs this many sub-tiles ahead
     static constexpr int NT = WM * WN * 64;       // threads
     static constexpr int RHO = T_MC / T_MA;
     static constexpr int MT = T_MC / 32;          // 32-row bands in the C tile
@@ -60,7 +67,7 @@ struct Shape {
     static constexpr int PB = T_N * 2;            // B rows are not padded: an XOR swizzle of the 16-byte chunks avoids the bank conflicts
     static constexpr int A_BYTES = T_MA * PA;
     static constexpr int B_BYTES = T_K * PB;
-    static constexpr int LDS_BYTES = 2 * A_BYTES + 2 * B_BYTES;
+    static constexpr int LDS_BYTES = AB * A_BYTES + 2 * B_BYTES;
     // staging work per thread: A in chunks of ACE mantissas (ACE/8 BFP16 blocks), B in chunks of 8 bf16
     static constexpr int ACE = (T_MA * T_K / NT >= 16) ? 16 : 8;
     static constexpr int A_CHUNKS = T_MA * T_K / ACE;
@@ -78,6 +85,7 @@ struct Shape {
     static constexpr int NBASE = (NTW < 4) ? NTW : 4;   // distinct per-lane read bases (the swizzle permutes 4 bands)
     static_assert(T_MC % T_MA == 0, "rho must be an integer");
     static_assert(PF >= 2 && (2 * RHO) % PF == 0, "prefetch distance: at least 2 (fetch and decode overlap), dividing two K-steps of sub-tiles");
+    static_assert(AB == 2 || (AB == 4 && PF >= 3 && (2 * RHO) % 4 == 0), "4 A buffers need rho >= 2 and a fetch distance of 3 or more");
     static_assert(128 % T_K == 0 && T_K % 32 == 0, "T_K must divide the 128-byte row padding of the mantissa plane; exponent dwords stay aligned");
     static_assert(T_MA % 32 == 0 && T_N % (32 * WN) == 0 && T_K % 16 == 0, "MFMA 32x32x16 granularity");
     static_assert(MT % WM == 0 && SMT % WM == 0, "every sub-tile must feed every wave row equally");
@@ -153,8 +161,8 @@ struct TileKernel {
     Rsrc rs;
     int tid, lane, wm, wn, m0, n0;
     // LDS byte addresses of this thread's staging writes and fragment reads, per buffer
-    char *a_wr[2], *b_wr[2];
-    const char *a_rd[2], *b_rd[2][S::NBASE];  // b_rd[buffer][column band mod 4]
+    char *a_wr[S::AB], *b_wr[2];
+    const char *a_rd[S::AB], *b_rd[2][S::NBASE];  // b_rd[buffer][column band mod 4]
     char *b_req[2];                    // LDS byte address of this wave's first 1 KiB B request, per buffer
     // Byte offsets of this thread's global loads relative to the current K-step.  They never
     // change: the K-step advance is applied to the (scalar) buffer descriptors instead, base up and
@@ -194,14 +202,17 @@ struct TileKernel {
         const int slot0 = __builtin_amdgcn_readfirstlane(wave) * S::B_PER_THREAD * 64;
         const int blk = lane >> 4, j = lane & 15, r = j >> 2;
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
+        for (int b = 0; b < S::AB; ++b) {
             char *a_base = lds + b * S::A_BYTES;
-            char *b_base = lds + 2 * S::A_BYTES + b * S::B_BYTES;
             a_wr[b] = a_base + a_row * S::PA + a_q * (S::ACE * 2);
-            b_req[b] = b_base + slot0 * 16;
-            b_wr[b] = b_req[b] + lane * 16;
             // A fragment: lane l reads row l%32 of a band, k = ks*16 + 8*(l/32) .. +7
             a_rd[b] = a_base + (wm * 32 + (lane & 31)) * S::PA + (lane >> 5) * 16;
+        }
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            char *b_base = lds + S::AB * S::A_BYTES + b * S::B_BYTES;
+            b_req[b] = b_base + slot0 * 16;
+            b_wr[b] = b_req[b] + lane * 16;
             // B fragment through ds_read_b64_tr_b16: within each group of 16 lanes, lane i addresses
             // 4 consecutive columns of row i/4 (8 bytes, half a chunk), and lane j receives column j
             // of those 4 rows.  The swizzle of row r (mod 4) permutes the chunk index, so each of the
@@ -434,18 +445,20 @@ struct TileKernel {
 
     // A fragment (band il of the sub-tile, k-slice ks).  Bands of the C tile are dealt round-robin
     // to the wave rows: this wave reads band il*WM + wm of the sub-tile.
-    template <int il, int ks>
+    // The fragments of consecutive bands (counted across sub-tiles) alternate between the two
+    // halves of afrag: `par` is that running band index mod 2.
+    template <int par, int il, int ks>
     ATB_DEV void read_a_frag(const char *a_src)
     {
-        afrag[il % 2][ks] = *reinterpret_cast<const bf16x8 *>(a_src + il * S::WM * 32 * S::PA + ks * 32);
+        afrag[par][ks] = *reinterpret_cast<const bf16x8 *>(a_src + il * S::WM * 32 * S::PA + ks * 32);
     }
 
-    template <int ks = 0>
+    template <int par, int ks = 0>
     ATB_DEV void read_first_band(const char *a_src)
     {
         if constexpr (ks < S::KS) {
-            read_a_frag<0, ks>(a_src);
-            read_first_band<ks + 1>(a_src);
+            read_a_frag<par, 0, ks>(a_src);
+            read_first_band<par, ks + 1>(a_src);
         }
     }
 
@@ -467,7 +480,7 @@ struct TileKernel {
         if constexpr (ATB_ABLATE & 4) {
             if constexpr (j >= n_la + n_lb) {
                 if constexpr (j < n_la + n_lb + S::NPAIR)
-                    decode_pair<(g + 1) % S::PF, (j - n_la - n_lb) / (S::ACE / 2), (j - n_la - n_lb) % (S::ACE / 2)>(a_wr[(g + 1) % 2]);
+                    decode_pair<(g + S::DA) % S::PF, (j - n_la - n_lb) / (S::ACE / 2), (j - n_la - n_lb) % (S::ACE / 2)>(a_wr[(g + S::DA) % S::AB]);
                 else
                     store_b_chunk<j - n_la - n_lb - S::NPAIR>(b_wr[kpar]);
             }
@@ -476,7 +489,7 @@ struct TileKernel {
         } else if constexpr (j < n_la + n_lb) {
             if constexpr (!(ATB_ABLATE & 512)) load_b_chunk<j - n_la>(kpar);
         } else if constexpr (j < n_la + n_lb + S::NPAIR) {
-            decode_pair<(g + 1) % S::PF, (j - n_la - n_lb) / (S::ACE / 2), (j - n_la - n_lb) % (S::ACE / 2)>(a_wr[(g + 1) % 2]);
+            decode_pair<(g + S::DA) % S::PF, (j - n_la - n_lb) / (S::ACE / 2), (j - n_la - n_lb) % (S::ACE / 2)>(a_wr[(g + S::DA) % S::AB]);
         } else {
             store_b_chunk<j - n_la - n_lb - S::NPAIR>(b_wr[kpar]);
         }
@@ -504,14 +517,20 @@ struct TileKernel {
             constexpr bool last_phase = (s + 1 == S::RHO);
             constexpr int nside = n_side<s>();
             constexpr int g = kpar * S::RHO + s;
+            constexpr int par = (g * S::PER + il) % 2;            // which half of afrag this band uses
             if constexpr (!(ATB_ABLATE & 32))
-                acc[local][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag[ks][nt], afrag[il % 2][ks],
+                acc[local][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag[ks][nt], afrag[par][ks],
                                                                         acc[local][nt], 0, 0, 0);
             else
-                acc[local][nt][0] += (float)bfrag[ks][nt][0] + (float)afrag[il % 2][ks][0];
+                acc[local][nt][0] += (float)bfrag[ks][nt][0] + (float)afrag[par][ks][0];
             ATB_FENCE();
             side_range<kpar, s, (m * nside) / S::NM, ((m + 1) * nside) / S::NM>();
-            if constexpr (nt == S::NTW - 1 && il + 1 < S::PER && !(ATB_ABLATE & 16)) read_a_frag<il + 1, ks>(a_rd[g % 2]);
+            if constexpr (nt == S::NTW - 1 && !(ATB_ABLATE & 16)) {
+                if constexpr (il + 1 < S::PER)
+                    read_a_frag<par ^ 1, il + 1, ks>(a_rd[g % S::AB]);
+                else if constexpr (S::AB == 4)      // first band of the next sub-tile, already complete in LDS
+                    read_a_frag<par ^ 1, 0, ks>(a_rd[(g + 1) % S::AB]);
+            }
             if constexpr (last_phase && il + 1 == S::PER && !(ATB_ABLATE & 2)) read_b_frag<ks, nt>(b_rd[kpar ^ 1]);
             ATB_FENCE();
             slots<kpar, s, m + 1>();
@@ -524,7 +543,7 @@ struct TileKernel {
     {
         if constexpr (s < S::RHO) {
             constexpr int g = kpar * S::RHO + s;
-            read_first_band(a_rd[g % 2]);
+            if constexpr (S::AB == 2) read_first_band<(g * S::PER) % 2>(a_rd[g % 2]);
             ATB_FENCE();
             ATB_STAMP(1);
             slots<kpar, s, 0>();
@@ -556,9 +575,11 @@ struct TileKernel {
         if constexpr (!VEC) store_b_all(b_wr[0]);
         load_b(1);
         store_a_all<0>(a_wr[0]);
+        if constexpr (S::AB == 4) store_a_all<1>(a_wr[1]);
         if constexpr (VEC) wait_vm<0>(); else store_b_all(b_wr[1]);
         __syncthreads();
         read_b_frags_all(b_rd[0]);
+        if constexpr (S::AB == 4) read_first_band<0>(a_rd[0]);
 
         // an odd number of K-steps is rounded up: the extra step multiplies by B rows >= K, which
         // read as zero
@@ -658,14 +679,16 @@ Instance make_instance()
 }
 
 const Instance g_instances[] = {
-    // T_MC = T_N = 256, T_K = 64: the sweep over rho = 1, 2, 4, 8
-    make_instance<Shape<256, 256, 64, 256, 2, 2, 2>>(),
-    make_instance<Shape<128, 256, 64, 256, 2, 2, 2>>(),
-    make_instance<Shape<64, 256, 64, 256, 2, 2, 2>>(),
-    make_instance<Shape<32, 256, 64, 256, 1, 4, 4>>(),
+    // T_MC = T_N = 256, T_K = 64: the sweep over rho = 1, 2, 4, 8.
+    // 8 waves (2 x 4, two per SIMD, 128 accumulator registers each) let one wave's decode and memory
+    // instructions issue while the other's MFMAs run; T_MA = 32 only feeds a 1 x 4 grid.
+    make_instance<Shape<256, 256, 64, 256, 2, 4, 2, 2>>(),
+    make_instance<Shape<128, 256, 64, 256, 2, 4, 2, 2>>(),
+    make_instance<Shape<64, 256, 64, 256, 2, 4, 4, 4>>(),
+    make_instance<Shape<32, 256, 64, 256, 1, 4, 4, 4>>(),
     // small tiles for small problems
-    make_instance<Shape<64, 64, 64, 64, 2, 2, 2>>(),
-    make_instance<Shape<32, 64, 64, 64, 1, 2, 2>>(),
+    make_instance<Shape<64, 64, 64, 64, 2, 2, 2, 2>>(),
+    make_instance<Shape<32, 64, 64, 64, 1, 2, 2, 2>>(),
 };
 
 }  // namespace

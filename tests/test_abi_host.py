@@ -49,7 +49,7 @@ def test_instances_and_create_validation():
     assert create(256, 256, 256, 32, 64, 64, 64) == 0 and h.value
     wg, th, lds = ctypes.c_int64(), ctypes.c_int(), ctypes.c_int()
     assert L.atb_gemm_launch_info(h, ctypes.byref(wg), ctypes.byref(th), ctypes.byref(lds)) == 0
-    assert wg.value == 16 and th.value in (128, 256) and 0 < lds.value <= 160 * 1024
+    assert wg.value == 16 and th.value in (128, 256, 512) and 0 < lds.value <= 160 * 1024
     L.atb_gemm_destroy(h)
     assert create(0, 256, 256, 32, 64, 64, 64) == 1 and not h.value          # M < 1
     assert create(256, 256, 252, 32, 64, 64, 64) == 1                         # K % 8
