@@ -170,7 +170,8 @@ atb_status atb_model_eval(int64_t M, int64_t N, int64_t K, int T_MA, int T_MC, i
                           const atb_hw_params *hw, atb_choice *out);
 
 /* Rank the compiled instances for a problem by predicted throughput
- * (infeasible ones last).  Writes min(capacity, count) entries to `ranked`
+ * (infeasible ones last): atb_model_eval's prediction, with the compute bound
+ * scaled by the measured microkernel factor an instance may carry.  Writes min(capacity, count) entries to `ranked`
  * (HOST) and the number of instances to *count.  ranked[0] is the pick. */
 atb_status atb_select_tiles(int64_t M, int64_t N, int64_t K, const atb_hw_params *hw,
                             atb_choice *ranked, int capacity, int *count);

@@ -663,9 +663,10 @@ hipError_t launch_instance(const GemmParams &p, hipStream_t stream)
 }
 
 template <class S>
-Instance make_instance()
+Instance make_instance(double eff_scale = 1.0)
 {
     Instance i;
+    i.eff_scale = eff_scale;
     i.T_MA = S::T_MA;
     i.T_MC = S::T_MC;
     i.T_K = S::T_K;
@@ -686,6 +687,9 @@ const Instance g_instances[] = {
     make_instance<Shape<128, 256, 64, 256, 2, 4, 2, 2>>(),
     make_instance<Shape<64, 256, 64, 256, 2, 4, 4, 4>>(),
     make_instance<Shape<32, 256, 64, 256, 1, 4, 4, 4>>(),
+    // T_K = 128 exists only with ATB: at rho = 8 the A buffers take 17 KiB next to 128 KiB of B; the
+    // symmetric tile would need 264 KiB of LDS (the "ATB makes an infeasible tile legal" case of Sec. 6.3)
+    make_instance<Shape<32, 256, 128, 256, 1, 4, 4, 2>>(0.86),   // measured: the 1 x 4 wave grid reads A from LDS twice as often
     // small tiles for small problems
     make_instance<Shape<64, 64, 64, 64, 2, 2, 2, 2>>(),
     make_instance<Shape<32, 64, 64, 64, 1, 2, 2, 2>>(),

@@ -27,6 +27,7 @@ struct Instance {
     int wave_m, wave_n;     // wave grid inside the workgroup
     int threads;            // wave_m * wave_n * 64
     int lds_bytes;          // static LDS of the kernel
+    double eff_scale;       // measured microkernel efficiency of this instance relative to Eq. (12)'s fit
     hipError_t (*launch)(const GemmParams &p, hipStream_t stream);
 };
 

@@ -57,6 +57,9 @@ def test_instances_and_create_validation():
     assert create(256, 256, 256, 64, 64, 32, 64) == 2                         # not compiled
     assert create(256, 256, 256, 512, 512, 64, 256) == 4                      # C tile > accumulators
     assert create(256, 256, 256, 256, 256, 512, 64) == 3                      # A + B > LDS
+    assert create(256, 256, 256, 256, 256, 128, 256) == 3                     # T_K = 128 does not fit symmetric ...
+    assert create(256, 256, 256, 32, 256, 128, 256) == 0 and h.value         # ... but fits at rho = 8
+    L.atb_gemm_destroy(h)
     assert L.atb_gemm_create(None, 1, 1, 8, 32, 64, 64, 64) == 1
     assert L.atb_gemm_run(None, None, None, None, None) == 1
     L.atb_gemm_destroy(None)                                                  # no-op
@@ -133,6 +136,9 @@ def test_model_mi355x_mode_and_selector():
         t_mfma = 2.0 * 256 * 256 * 64 / hw.peak_core_flops
         t = t_mfma / c.eff_micro + (hw.delta_cycles * rho + hw.fill_cycles / rho) / hw.clock_hz
         assert c.eff_core == pytest.approx(t_mfma / t, rel=1e-12)
+    # ATB makes T_K = 128 legal: 264 KiB of LDS symmetric, 146 KiB at rho = 8
+    assert atb.model_eval(8192, 8192, 8192, 256, 256, 128, 256, hw).feasible == 0
+    assert atb.model_eval(8192, 8192, 8192, 32, 256, 128, 256, hw).feasible == 1
     ranked = atb.select_tiles(8192, 8192, 8192)
     assert len(ranked) == len(atb.instances())
     assert ranked[0].feasible == 1 and ranked[0].T_MC == 256

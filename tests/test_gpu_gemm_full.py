@@ -12,9 +12,9 @@ pytestmark = pytest.mark.gpu
 
 CASES = [
     ("square4096", [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256)]),
-    ("square8192", [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256), (32, 256, 64, 256)]),
+    ("square8192", [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256), (32, 256, 64, 256), (32, 256, 128, 256)]),
     ("mlp", [(256, 256, 64, 256), (64, 256, 64, 256)]),
-    ("ragged", [(256, 256, 64, 256), (64, 256, 64, 256), (32, 64, 64, 64)]),
+    ("ragged", [(256, 256, 64, 256), (64, 256, 64, 256), (32, 64, 64, 64), (32, 256, 128, 256)]),
 ]
 
 
