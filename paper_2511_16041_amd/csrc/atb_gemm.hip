@@ -122,11 +122,11 @@ constexpr int kOutOfRange = (int)0x80000000;     // a byte offset no buffer of o
 // Cycle stamps for kernel tuning; compiled out of the library (ATB_TRACE is defined only by the
 // developer's own timing harness, which also supplies atb_trace_buf).
 #ifdef ATB_TRACE
-__device__ unsigned long long atb_trace_acc[16];
+__device__ unsigned long long atb_trace_acc[16 * 8];
 #define ATB_TRACE_DECL unsigned long long trace_prev = 0, trace_sum[8] = {}
 #define ATB_STAMP(id)                                                              \
     do {                                                                           \
-        if (blockIdx.x == 0 && threadIdx.x < 64) {                                 \
+        if (blockIdx.x == 0) {                                                     \
             unsigned long long now = __builtin_amdgcn_s_memtime();                 \
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                     \
             trace_sum[id] += now - trace_prev;                                     \
@@ -135,8 +135,8 @@ __device__ unsigned long long atb_trace_acc[16];
     } while (0)
 #define ATB_TRACE_FLUSH()                                                          \
     do {                                                                           \
-        if (blockIdx.x == 0 && threadIdx.x == 0)                                   \
-            for (int i = 0; i < 8; ++i) atb_trace_acc[i] = trace_sum[i];           \
+        if (blockIdx.x == 0 && threadIdx.x % 64 == 0 && threadIdx.x / 64 < 16)      \
+            for (int i = 0; i < 8; ++i) atb_trace_acc[(threadIdx.x / 64) * 8 + i] = trace_sum[i]; \
     } while (0)
 #else
 #define ATB_TRACE_DECL
@@ -150,10 +150,11 @@ __device__ unsigned long long atb_trace_acc[16];
 // Time line (g = kt*RHO + s numbers the A sub-tiles):
 //   A sub-tile g   : fetched from memory in phase g-PF into register set g % PF, decoded into LDS
 //                    buffer g % 2 during phase g-1, consumed by the microkernel of phase g.
-//   B tile kt      : fetched in the first phase of K-step kt-2, written to LDS buffer kt % 2 in the
-//                    last phase of K-step kt-2, read into the waves' fragment registers during the
-//                    last band of K-step kt-1 (each fragment right after its last use), consumed in
-//                    K-step kt.
+//   B tile kt      : requested in the first phase of K-step kt-2 straight into LDS buffer kt % 2
+//                    (N % 8 != 0: into registers, written to LDS in the last phase of K-step kt-2),
+//                    awaited before the last barrier that precedes the last band of K-step kt-1,
+//                    read into the waves' fragment registers during that band (each fragment
+//                    right after its last use), consumed in K-step kt.
 // The K loop is unrolled by two so that every buffer and register-set index is a constant.
 template <class S, bool VEC>
 struct TileKernel {
@@ -291,7 +292,7 @@ struct TileKernel {
             a_mant[set][i] = intx4{t.x, t.y, 0, 0};
         }
         // the aligned dword that holds this chunk's exponent byte(s): sub-dword loads are far slower
-        a_expo[set][i] = __builtin_amdgcn_raw_buffer_load_b32(rs.ae, a_eoff[sub][i], 0, 0);
+        if constexpr (!(ATB_ABLATE & 1024)) a_expo[set][i] = __builtin_amdgcn_raw_buffer_load_b32(rs.ae, a_eoff[sub][i], 0, 0);
         if constexpr (sub == S::RHO - 1 && i == S::A_PER_THREAD - 1 && !(ATB_ABLATE & 128)) {
             am_ptr += S::T_K;
             ae_ptr += S::T_K / 8;
@@ -477,17 +478,10 @@ struct TileKernel {
     {
         constexpr int g = kpar * S::RHO + s;
         constexpr int n_la = S::A_PER_THREAD, n_lb = (s == 0 ? S::B_PER_THREAD : 0);
-        if constexpr (ATB_ABLATE & 4) {
-            if constexpr (j >= n_la + n_lb) {
-                if constexpr (j < n_la + n_lb + S::NPAIR)
-                    decode_pair<(g + S::DA) % S::PF, (j - n_la - n_lb) / (S::ACE / 2), (j - n_la - n_lb) % (S::ACE / 2)>(a_wr[(g + S::DA) % S::AB]);
-                else
-                    store_b_chunk<j - n_la - n_lb - S::NPAIR>(b_wr[kpar]);
-            }
-        } else if constexpr (j < n_la) {
-            if constexpr (!(ATB_ABLATE & 256)) load_a_chunk<g % S::PF, (s + S::PF) % S::RHO, j>();
-        } else if constexpr (j < n_la + n_lb) {
-            if constexpr (!(ATB_ABLATE & 512)) load_b_chunk<j - n_la>(kpar);
+        if constexpr (j < n_lb) {
+            if constexpr (!(ATB_ABLATE & 512)) load_b_chunk<j>(kpar);
+        } else if constexpr (j < n_lb + n_la) {
+            if constexpr (!(ATB_ABLATE & 256)) load_a_chunk<g % S::PF, (s + S::PF) % S::RHO, j - n_lb>();
         } else if constexpr (j < n_la + n_lb + S::NPAIR) {
             decode_pair<(g + S::DA) % S::PF, (j - n_la - n_lb) / (S::ACE / 2), (j - n_la - n_lb) % (S::ACE / 2)>(a_wr[(g + S::DA) % S::AB]);
         } else {
@@ -548,9 +542,15 @@ struct TileKernel {
             ATB_STAMP(1);
             slots<kpar, s, 0>();
             ATB_STAMP(2);
-            // the B tile requested in the first phase must have landed in LDS before the barrier
-            // that ends the K-step; only the A requests of the later phases are younger
-            if constexpr (VEC && s + 1 == S::RHO) wait_vm<(S::RHO - 1) * S::A_PER_THREAD * 2>();
+            // The B tile requested (straight into LDS) in the first phase of a K-step is read in the
+            // last band of the next K-step, so the last barrier before that band has to publish it.
+            // rho = 1: that is the barrier ending the K-step of the request; only the A requests
+            // issued after it are younger.  rho >= 2: the barrier ending the last-but-one phase of
+            // the next K-step, which leaves the tile almost two K-steps to arrive; younger are the
+            // A requests of 2 rho - 1 phases and the next B tile's requests.
+            if constexpr (VEC && S::RHO == 1) wait_vm<S::A_PER_THREAD * 2>();
+            if constexpr (VEC && S::RHO >= 2 && s == S::RHO - 2)
+                wait_vm<(2 * S::RHO - 1) * S::A_PER_THREAD * 2 + S::B_PER_THREAD>();
             if constexpr (!(ATB_ABLATE & 64)) switch_barrier();   // the "kernel switch" of the ATB nest
             ATB_STAMP(3);
             phases<kpar, s + 1>();
@@ -579,6 +579,8 @@ struct TileKernel {
         if constexpr (VEC) wait_vm<0>(); else store_b_all(b_wr[1]);
         __syncthreads();
         read_b_frags_all(b_rd[0]);
+        // B buffer 0 is refilled from the first phase on: every wave must have its fragments first
+        switch_barrier();
         if constexpr (S::AB == 4) read_first_band<0>(a_rd[0]);
 
         // an odd number of K-steps is rounded up: the extra step multiplies by B rows >= K, which
@@ -683,13 +685,15 @@ const Instance g_instances[] = {
     // T_MC = T_N = 256, T_K = 64: the sweep over rho = 1, 2, 4, 8.
     // 8 waves (2 x 4, two per SIMD, 128 accumulator registers each) let one wave's decode and memory
     // instructions issue while the other's MFMAs run; T_MA = 32 only feeds a 1 x 4 grid.
+    // The A fetch runs about one and a half K-steps ahead of its use at every rho (PF phases): a
+    // shorter distance leaves the memory latency under load exposed (measured: +6 % from PF 2 -> 4 at rho = 2).
     make_instance<Shape<256, 256, 64, 256, 2, 4, 2, 2>>(),
-    make_instance<Shape<128, 256, 64, 256, 2, 4, 2, 2>>(),
+    make_instance<Shape<128, 256, 64, 256, 2, 4, 4, 4>>(),
     make_instance<Shape<64, 256, 64, 256, 2, 4, 4, 4>>(),
-    make_instance<Shape<32, 256, 64, 256, 1, 4, 4, 4>>(),
+    make_instance<Shape<32, 256, 64, 256, 1, 4, 8, 4>>(),
     // T_K = 128 exists only with ATB: at rho = 8 the A buffers take 17 KiB next to 128 KiB of B; the
     // symmetric tile would need 264 KiB of LDS (the "ATB makes an infeasible tile legal" case of Sec. 6.3)
-    make_instance<Shape<32, 256, 128, 256, 1, 4, 4, 2>>(0.86),   // measured: the 1 x 4 wave grid reads A from LDS twice as often
+    make_instance<Shape<32, 256, 128, 256, 1, 4, 8, 2>>(0.86),   // measured: the 1 x 4 wave grid reads A from LDS twice as often
     // small tiles for small problems
     make_instance<Shape<64, 64, 64, 64, 2, 2, 2, 2>>(),
     make_instance<Shape<32, 64, 64, 64, 1, 2, 2, 2>>(),
