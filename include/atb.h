@@ -85,8 +85,11 @@ atb_status atb_gemm_run(const atb_gemm *g, const void *A_bfp, const void *B_bf16
 
 void atb_gemm_destroy(atb_gemm *g);
 
-/* Launch geometry of a plan, for benches and tests: number of workgroups,
- * threads per workgroup, static LDS bytes per workgroup. Any pointer may be NULL. */
+/* Launch geometry of a plan, for benches and tests: number of C tiles the
+ * launch walks, rounded up to a multiple of 8 (the grid is persistent: it has
+ * min(that, workgroups resident on the chip) workgroups, each looping over its
+ * tiles), threads per workgroup, static LDS bytes per workgroup. Any pointer
+ * may be NULL. */
 atb_status atb_gemm_launch_info(const atb_gemm *g, int64_t *workgroups, int *threads, int *lds_bytes);
 
 /* The compiled (T_MA, T_MC, T_K, T_N) instances. */

@@ -27,6 +27,8 @@
 // the first operand and the A fragment as the second, so a lane of the result
 // holds one row m (= l % 32) and 16 columns n = 8*(v/4) + 4*(l/32) + v%4,
 // i.e. groups of 4 consecutive columns -> 8-byte bf16 stores.
+#include <algorithm>
+
 #include "atb_internal.h"
 
 namespace atb {
@@ -541,7 +543,12 @@ struct TileKernel {
             else
                 acc[local][nt][0] += (float)bfrag[ks][nt][0] + (float)afrag[par][ks][0];
             ATB_FENCE();
-            side_range<kpar, s, (m * nside) / S::NM, ((m + 1) * nside) / S::NM>();
+            // the last eighth of the slots carries no side work, so that the LDS stores of the decode
+            // have drained when the wave reaches the switch barrier
+            constexpr int NS = S::NM - S::NM / 8;
+            constexpr int j0 = (m * nside) / NS < nside ? (m * nside) / NS : nside;
+            constexpr int j1 = ((m + 1) * nside) / NS < nside ? ((m + 1) * nside) / NS : nside;
+            side_range<kpar, s, j0, j1>();
             if constexpr (nt == S::NTW - 1 && !(ATB_ABLATE & 16)) {
                 if constexpr (il + 1 < S::PER)
                     read_a_frag<par ^ 1, il + 1, ks>(a_rd[g % S::AB]);
@@ -615,6 +622,9 @@ struct TileKernel {
             phases<1, 0>();
         }
         ATB_TRACE_FLUSH();
+        // the requests for the two K-steps past the end (they read zeros) must not be in flight when
+        // the next tile of this workgroup re-uses the registers and LDS buffers they target
+        wait_vm<0>();
         store_c();
     }
 
@@ -653,36 +663,62 @@ struct TileKernel {
     }
 };
 
+// Workgroup -> C tiles.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2); XCD x
+// owns the contiguous run of tiles [x * per_xcd, (x + 1) * per_xcd), walked in bands of group_m tile
+// rows so that the workgroups resident on one XCD share few distinct A row panels and B column panels.
+// For the large tiles the grid is persistent: it holds only as many workgroups as fit on the chip at
+// once, and workgroup b serves tiles b / 8, b / 8 + gridDim.x / 8, ... of its XCD's run.  The stores of one tile's epilogue
+// then drain while the next tile's first requests are already in flight, and no tile waits for a
+// workgroup launch.
+template <class S, bool VEC, int ROLE>
+__device__ __forceinline__ void tile_loop(const GemmParams &p, char *lds)
+{
+    const int total = p.tiles_m * p.tiles_n;
+    const int per_xcd = (total + 7) / 8;
+    const int stride = (int)gridDim.x / 8;
+    const int band_sz = p.group_m * p.tiles_n;
+    for (int t = (int)blockIdx.x / 8; t < per_xcd; t += stride) {
+        const int logical = (int)(blockIdx.x % 8) * per_xcd + t;
+        if (logical >= total) break;
+        const int band = logical / band_sz, in_band = logical % band_sz;
+        const int rows_here = min(p.group_m, p.tiles_m - band * p.group_m);
+        const int tm = band * p.group_m + in_band % rows_here;
+        const int tn = in_band / rows_here;
+        TileKernel<S, VEC, ROLE> tile(p, lds, tm * S::T_MC, tn * S::T_N);
+        tile.run();
+    }
+}
+
 template <class S, bool VEC>
 __global__ void __launch_bounds__(S::NT) atb_gemm_kernel(const GemmParams p)
 {
     __shared__ __attribute__((aligned(16))) char lds[S::LDS_BYTES];
-
-    // Workgroup -> C tile.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2);
-    // give each XCD a contiguous run of tiles, and walk tiles in bands of group_m tile rows so that
-    // the workgroups resident on one XCD share few distinct A row panels and B column panels.
-    const int total = p.tiles_m * p.tiles_n;
-    const int per_xcd = (total + 7) / 8;
-    const int logical = (int)(blockIdx.x % 8) * per_xcd + (int)(blockIdx.x / 8);
-    if (logical >= total) return;
-    const int band_sz = p.group_m * p.tiles_n;
-    const int band = logical / band_sz, in_band = logical % band_sz;
-    const int rows_here = min(p.group_m, p.tiles_m - band * p.group_m);
-    const int tm = band * p.group_m + in_band % rows_here;
-    const int tn = in_band / rows_here;
-
     if constexpr (S::NT == 512) {
-        if (threadIdx.x < 256) {        // wave-uniform: both sides execute the same barriers
-            TileKernel<S, VEC, 1> t(p, lds, tm * S::T_MC, tn * S::T_N);
-            t.run();
-        } else {
-            TileKernel<S, VEC, 2> t(p, lds, tm * S::T_MC, tn * S::T_N);
-            t.run();
-        }
+        // wave-uniform branch; both sides execute the same sequence of barriers
+        if (threadIdx.x < 256)
+            tile_loop<S, VEC, 1>(p, lds);
+        else
+            tile_loop<S, VEC, 2>(p, lds);
     } else {
-        TileKernel<S, VEC, 0> t(p, lds, tm * S::T_MC, tn * S::T_N);
-        t.run();
+        tile_loop<S, VEC, 0>(p, lds);
     }
+}
+
+// Workgroups of this kernel that one CU holds at a time (LDS- or register-limited), times the CUs.
+template <class S, bool VEC>
+int resident_workgroups()
+{
+    static int cached = 0;
+    if (cached == 0) {
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, atb_gemm_kernel<S, VEC>, S::NT, 0) != hipSuccess ||
+            cus < 8 || per_cu < 1)
+            return 0;
+        cached = cus * per_cu;
+    }
+    return cached;
 }
 
 template <class S>
@@ -690,10 +726,17 @@ hipError_t launch_instance(const GemmParams &p, hipStream_t stream)
 {
     const int total = p.tiles_m * p.tiles_n;
     const int per_xcd = (total + 7) / 8;
-    if ((p.N % 8) == 0)
-        hipLaunchKernelGGL((atb_gemm_kernel<S, true>), dim3(per_xcd * 8), dim3(S::NT), 0, stream, p);
+    const bool vec = (p.N % 8) == 0;
+    const int resident = vec ? resident_workgroups<S, true>() : resident_workgroups<S, false>();
+    if (resident == 0) return hipErrorInvalidDevice;
+    // Small tiles keep one workgroup per tile: several of them share a CU and overlap each other's
+    // prologue and epilogue already, and the hardware dispatcher balances them better than a fixed walk.
+    constexpr bool persistent = S::T_MC * S::T_N >= 256 * 256;
+    const int slots = persistent ? std::min(per_xcd, resident / 8) : per_xcd;     // workgroups per XCD
+    if (vec)
+        hipLaunchKernelGGL((atb_gemm_kernel<S, true>), dim3(slots * 8), dim3(S::NT), 0, stream, p);
     else
-        hipLaunchKernelGGL((atb_gemm_kernel<S, false>), dim3(per_xcd * 8), dim3(S::NT), 0, stream, p);
+        hipLaunchKernelGGL((atb_gemm_kernel<S, false>), dim3(slots * 8), dim3(S::NT), 0, stream, p);
     return hipGetLastError();
 }
 
