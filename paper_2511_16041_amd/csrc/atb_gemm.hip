@@ -771,7 +771,7 @@ const Instance g_instances[] = {
     make_instance<Shape<32, 256, 64, 256, 1, 4, 8, 4>>(),
     // T_K = 128 exists only with ATB: at rho = 8 the A buffers take 17 KiB next to 128 KiB of B; the
     // symmetric tile would need 264 KiB of LDS (the "ATB makes an infeasible tile legal" case of Sec. 6.3)
-    make_instance<Shape<32, 256, 128, 256, 1, 4, 8, 2>>(0.86),   // measured: the 1 x 4 wave grid reads A from LDS twice as often
+    make_instance<Shape<32, 256, 128, 256, 1, 4, 8, 2>>(0.96),   // measured against the fit, which is dominated by the 2 x 4 grid instances
     // small tiles for small problems
     make_instance<Shape<64, 64, 64, 64, 2, 2, 2, 2>>(),
     make_instance<Shape<32, 64, 64, 64, 1, 2, 2, 2>>(),

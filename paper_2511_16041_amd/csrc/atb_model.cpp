@@ -60,14 +60,14 @@ extern "C" void atb_hw_params_mi355x(atb_hw_params *hw)
     hw->buffer_bytes = 160.0 * 1024.0;           // LDS per CU
     hw->acc_bytes = 256.0 * 1024.0;              // 4 waves x 256 accumulator VGPRs x 64 lanes x 4 B
     // Least-squares fit to the measured K-step times of the 256x256x64 instances at rho = 1, 2, 4, 8
-    // on 8192^3 (in cycles of the nominal 2.4 GHz clock): 3575 + 166 rho + 1147 / rho, against 2048
-    // cycles of MFMA issue, i.e. Eff_micro(64) = 0.573.  T_K = 128 measured no better than 64, so the
+    // on 8192^3 (in cycles of the nominal 2.4 GHz clock): 3914 + 153 rho + 448 / rho, against 2048
+    // cycles of MFMA issue, i.e. Eff_micro(64) = 0.523.  T_K = 128 measured no better than 64, so the
     // fit saturates early (small eps): Eff_micro ~ 1 / II.
-    hw->delta_cycles = 166.0;
-    hw->fill_cycles = 1147.0;
+    hw->delta_cycles = 153.0;
+    hw->fill_cycles = 448.0;
     hw->eta = 1.0;
     hw->eps = 0.4;
-    hw->II = 1.739;
+    hw->II = 1.905;
     hw->a_bytes = 1.125;                         // A BFP16: 9 bytes per 8 elements
     hw->b_bytes = 2.0;
     hw->c_bytes = 2.0;
