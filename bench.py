@@ -202,6 +202,19 @@ def main():
             out["model_vs_measured_rank_spearman"] = round(spearman([s["model_tflops"] for s in fam],
                                                                     [s["tflops"] for s in fam]), 3)
 
+    if not args.no_sweep and (N % 8) == 0 and tiles in ((256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256)):
+        # the other storage formats of the same tile (B handed over as B^T in BFP16, C written as BFP16)
+        Bt_bfp = atb.bfp16_quantize(B.float().t().contiguous())
+        fmts = []
+        for bf, cf in (("bfp16", "bf16"), ("bf16", "bfp16"), ("bfp16", "bfp16")):
+            p = atb.Gemm(M, N, K, *tiles, b_format=bf, c_format=cf)
+            Cx = None if cf == "bf16" else torch.empty(atb.bfp16_bytes(M, N), dtype=torch.uint8, device="cuda")
+            _, kms = time_plan(p, A_bfp, Bt_bfp if bf == "bfp16" else B, Cx if Cx is not None else C, max(5, args.steps // 2), 5)
+            p.close()
+            fmts.append({"A": "bfp16", "B": bf, "C": cf, "accumulate": "fp32", "tflops": round(flop / (kms * 1e-3) / 1e12, 1)})
+        del Bt_bfp
+        out["storage_formats"] = fmts
+
     if not args.no_cpu:
         import oracle
         lay = atb.bfp16_layout(M, K)

@@ -85,6 +85,34 @@ atb_status atb_gemm_run(const atb_gemm *g, const void *A_bfp, const void *B_bf16
 
 void atb_gemm_destroy(atb_gemm *g);
 
+/* Storage formats of the B and C operands (Sec. 6.1 of the paper lists three
+ * precision configurations; its Configs 2 and 3 store every operand as BFP16).
+ * A is always BFP16; accumulation is always fp32 in the MFMA accumulators. */
+typedef enum atb_format {
+    ATB_FMT_BF16 = 0,
+    ATB_FMT_BFP16 = 1
+} atb_format;
+
+/* atb_gemm_create with a storage format per operand.  The plan is run with
+ * atb_gemm_run, whose B and C pointers then mean:
+ *   b_format BF16 : B, K x N bf16 row-major (as in atb_gemm_create).
+ *   b_format BFP16: B^T, N x K, as a BFP16 buffer with the layout
+ *                   atb_bfp16_layout(N, K), i.e. blocks of 8 along K (the
+ *                   reduction dimension, as the format requires, Sec. 2.4)
+ *                   with the K index contiguous; atb_bfp16_quantize of a
+ *                   row-major N x K fp32 matrix produces it.
+ *   c_format BF16 : C, M x N bf16 row-major.
+ *   c_format BFP16: C as a BFP16 buffer with the layout atb_bfp16_layout(M, N)
+ *                   (blocks of 8 along N), quantised from the fp32
+ *                   accumulators by the same rule as atb_bfp16_quantize;
+ *                   rows are fully written including their zero padding.
+ * Formats other than (BF16, BF16) need N % 8 == 0 and one of the instances
+ * with T_MC = T_N = 256, T_K = 64, T_MA in {256, 128, 64}; otherwise
+ * ATB_ERR_INVALID_ARG / ATB_ERR_BAD_TILE.  All else as atb_gemm_create. */
+atb_status atb_gemm_create_fmt(atb_gemm **out, int64_t M, int64_t N, int64_t K,
+                               int T_MA, int T_MC, int T_K, int T_N,
+                               atb_format b_format, atb_format c_format);
+
 /* Launch geometry of a plan, for benches and tests: number of C tiles the
  * launch walks, rounded up to a multiple of 8 (the grid is persistent: it has
  * min(that, workgroups resident on the chip) workgroups, each looping over its

@@ -132,6 +132,15 @@ def gemm_tiled(mant, expo, B_bits, T_MA: int, T_MC: int, T_K: int, T_N: int):
     return C, int(sw.value)
 
 
+def bfp16_as_bf16_bits(mant: np.ndarray, expo: np.ndarray) -> np.ndarray:
+    """BFP16 values as bf16 bit patterns.  Exact: m * 2^(E-133) with |m| <= 127 has at most 7
+    significant bits (Sec. 2.4), bf16 keeps 8; asserted rather than assumed."""
+    v = decode(mant, expo)
+    bits = bf16_from_double(v)
+    assert np.array_equal(bf16_to_double(bits), v), "a BFP16 value outside the bf16 range"
+    return bits
+
+
 def tolerance(T: np.ndarray) -> np.ndarray:
     """Acceptance bound per element: 2^-7 * sum_k |a||b| + 1e-6."""
     return T * 2.0 ** -7 + 1e-6

@@ -57,7 +57,7 @@ class Bfp16Layout(ctypes.Structure):
 
 # every symbol include/atb.h declares
 EXPORTS = [
-    "atb_status_string", "atb_last_hip_error", "atb_gemm_create", "atb_gemm_run", "atb_gemm_destroy",
+    "atb_status_string", "atb_last_hip_error", "atb_gemm_create", "atb_gemm_create_fmt", "atb_gemm_run", "atb_gemm_destroy",
     "atb_gemm_launch_info", "atb_instance_count", "atb_instance_get", "atb_bfp16_layout", "atb_bfp16_bytes",
     "atb_bfp16_quantize", "atb_bfp16_decode", "atb_hw_params_xdna2", "atb_hw_params_mi355x",
     "atb_model_eval", "atb_select_tiles",
@@ -78,6 +78,8 @@ def lib() -> ctypes.CDLL:
     L.atb_last_hip_error.restype = ci
     L.atb_gemm_create.restype = ci
     L.atb_gemm_create.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci, ci, ci, ci]
+    L.atb_gemm_create_fmt.restype = ci
+    L.atb_gemm_create_fmt.argtypes = [ctypes.POINTER(vp), i64, i64, i64, ci, ci, ci, ci, ci, ci]
     L.atb_gemm_run.restype = ci
     L.atb_gemm_run.argtypes = [vp, vp, vp, vp, vp]
     L.atb_gemm_destroy.restype = None
@@ -196,26 +198,46 @@ class LaunchInfo:
     lds_bytes: int
 
 
-class Gemm:
-    """A plan from atb_gemm_create; run() launches it asynchronously."""
+FORMATS = {"bf16": 0, "bfp16": 1}      # atb_format
 
-    def __init__(self, M: int, N: int, K: int, T_MA: int, T_MC: int, T_K: int, T_N: int):
+
+class Gemm:
+    """A plan from atb_gemm_create / atb_gemm_create_fmt; run() launches it asynchronously.
+
+    b_format "bfp16": run() takes B^T (N x K) as a BFP16 buffer (bfp16_quantize of the N x K matrix);
+    c_format "bfp16": run() returns C as a BFP16 buffer with the layout bfp16_layout(M, N)."""
+
+    def __init__(self, M: int, N: int, K: int, T_MA: int, T_MC: int, T_K: int, T_N: int,
+                 b_format: str = "bf16", c_format: str = "bf16"):
         self._h = ctypes.c_void_p()
         self.shape = (M, N, K)
         self.tiles = (T_MA, T_MC, T_K, T_N)
-        _check(lib().atb_gemm_create(ctypes.byref(self._h), M, N, K, T_MA, T_MC, T_K, T_N), "atb_gemm_create")
+        self.b_format, self.c_format = b_format, c_format
+        if b_format == "bf16" and c_format == "bf16":
+            _check(lib().atb_gemm_create(ctypes.byref(self._h), M, N, K, T_MA, T_MC, T_K, T_N), "atb_gemm_create")
+        else:
+            _check(lib().atb_gemm_create_fmt(ctypes.byref(self._h), M, N, K, T_MA, T_MC, T_K, T_N,
+                                             FORMATS[b_format], FORMATS[c_format]), "atb_gemm_create_fmt")
 
-    def run(self, A_bfp, B_bf16, C_bf16=None, stream=None):
+    def run(self, A_bfp, B, C=None, stream=None):
         import torch
         M, N, K = self.shape
         assert A_bfp.is_cuda and A_bfp.dtype == torch.uint8 and A_bfp.numel() == bfp16_bytes(M, K)
-        assert B_bf16.is_cuda and B_bf16.dtype == torch.bfloat16 and tuple(B_bf16.shape) == (K, N) and B_bf16.is_contiguous()
-        if C_bf16 is None:
-            C_bf16 = torch.empty((M, N), dtype=torch.bfloat16, device=A_bfp.device)
-        assert C_bf16.dtype == torch.bfloat16 and tuple(C_bf16.shape) == (M, N) and C_bf16.is_contiguous()
-        _check(lib().atb_gemm_run(self._h, ctypes.c_void_p(A_bfp.data_ptr()), ctypes.c_void_p(B_bf16.data_ptr()),
-                                  ctypes.c_void_p(C_bf16.data_ptr()), _stream_ptr(stream)), "atb_gemm_run")
-        return C_bf16
+        if self.b_format == "bf16":
+            assert B.is_cuda and B.dtype == torch.bfloat16 and tuple(B.shape) == (K, N) and B.is_contiguous()
+        else:
+            assert B.is_cuda and B.dtype == torch.uint8 and B.numel() == bfp16_bytes(N, K)
+        if self.c_format == "bf16":
+            if C is None:
+                C = torch.empty((M, N), dtype=torch.bfloat16, device=A_bfp.device)
+            assert C.dtype == torch.bfloat16 and tuple(C.shape) == (M, N) and C.is_contiguous()
+        else:
+            if C is None:
+                C = torch.empty(bfp16_bytes(M, N), dtype=torch.uint8, device=A_bfp.device)
+            assert C.dtype == torch.uint8 and C.numel() == bfp16_bytes(M, N)
+        _check(lib().atb_gemm_run(self._h, ctypes.c_void_p(A_bfp.data_ptr()), ctypes.c_void_p(B.data_ptr()),
+                                  ctypes.c_void_p(C.data_ptr()), _stream_ptr(stream)), "atb_gemm_run")
+        return C
 
     def launch_info(self) -> LaunchInfo:
         wg, th, lds = ctypes.c_int64(), ctypes.c_int(), ctypes.c_int()

@@ -7,7 +7,10 @@
 struct atb_gemm {
     int64_t M, N, K;
     int instance;
-    atb_bfp16_layout_t layout;
+    int b_format, c_format;
+    atb_bfp16_layout_t layout;     // A
+    atb_bfp16_layout_t layout_b;   // B^T when b_format is BFP16
+    atb_bfp16_layout_t layout_c;   // C when c_format is BFP16
     atb::GemmParams proto;   // everything but the pointers
 };
 
@@ -98,9 +101,22 @@ extern "C" atb_status atb_bfp16_decode(const void *A_bfp, void *A_bf16, int64_t 
 extern "C" atb_status atb_gemm_create(atb_gemm **out, int64_t M, int64_t N, int64_t K,
                                       int T_MA, int T_MC, int T_K, int T_N)
 {
+    return atb_gemm_create_fmt(out, M, N, K, T_MA, T_MC, T_K, T_N, ATB_FMT_BF16, ATB_FMT_BF16);
+}
+
+extern "C" atb_status atb_gemm_create_fmt(atb_gemm **out, int64_t M, int64_t N, int64_t K,
+                                          int T_MA, int T_MC, int T_K, int T_N,
+                                          atb_format b_format, atb_format c_format)
+{
     if (!out) return ATB_ERR_INVALID_ARG;
     *out = nullptr;
     if (M < 1 || N < 1 || K < 8 || (K % 8) != 0) return ATB_ERR_INVALID_ARG;
+    if ((b_format != ATB_FMT_BF16 && b_format != ATB_FMT_BFP16) || (c_format != ATB_FMT_BF16 && c_format != ATB_FMT_BFP16))
+        return ATB_ERR_INVALID_ARG;
+    const bool other_fmt = (b_format != ATB_FMT_BF16 || c_format != ATB_FMT_BF16);
+    if (other_fmt && (N % 8) != 0) return ATB_ERR_INVALID_ARG;
+    if (N * atb::round_up(K, 128) >= ((int64_t)1 << 31) || M * atb::round_up(N, 128) >= ((int64_t)1 << 31))
+        return ATB_ERR_INVALID_ARG;
     // 32-bit element offsets inside the kernel: keep every plane below 2^31 elements
     if (M > (1 << 24) || N > (1 << 24) || K > (1 << 24) || M * N >= ((int64_t)1 << 31) ||
         M * atb::round_up(K, 128) >= ((int64_t)1 << 31) || K * N >= ((int64_t)1 << 31))
@@ -113,14 +129,23 @@ extern "C" atb_status atb_gemm_create(atb_gemm **out, int64_t M, int64_t N, int6
     if ((int64_t)2 * 2 * T_MA * T_K + (int64_t)2 * 2 * T_K * T_N > 160 * 1024) return ATB_ERR_LDS_BUDGET;
     const int idx = atb::find_instance(T_MA, T_MC, T_K, T_N);
     if (idx < 0) return ATB_ERR_BAD_TILE;
+    if (other_fmt && atb::instance(idx).launch_fmt == nullptr) return ATB_ERR_BAD_TILE;
 
     atb_gemm *g = new (std::nothrow) atb_gemm;
     if (!g) return ATB_ERR_NOMEM;
     g->M = M; g->N = N; g->K = K;
     g->instance = idx;
+    g->b_format = (int)b_format;
+    g->c_format = (int)c_format;
     atb_bfp16_layout(M, K, &g->layout);
+    atb_bfp16_layout(N, K, &g->layout_b);
+    g->layout_c = atb_bfp16_layout_t{0, 0, 0, 0};
+    if (c_format == ATB_FMT_BFP16) atb_bfp16_layout(M, N, &g->layout_c);
     atb::GemmParams &p = g->proto;
     p.Am = nullptr; p.Ae = nullptr; p.B = nullptr; p.C = nullptr;
+    p.Bm = nullptr; p.Be = nullptr; p.Cm = nullptr; p.Ce = nullptr;
+    p.ldbm = (int)g->layout_b.ldm; p.ldbe = (int)g->layout_b.lde;
+    p.ldcm = (int)g->layout_c.ldm; p.ldce = (int)g->layout_c.lde;
     p.M = (int)M; p.N = (int)N; p.K = (int)K;
     p.ldm = (int)g->layout.ldm;
     p.lde = (int)g->layout.lde;
@@ -138,9 +163,22 @@ extern "C" atb_status atb_gemm_run(const atb_gemm *g, const void *A_bfp, const v
     atb::GemmParams p = g->proto;
     p.Am = static_cast<const int8_t *>(A_bfp);
     p.Ae = static_cast<const uint8_t *>(A_bfp) + g->layout.exp_off;
-    p.B = static_cast<const uint16_t *>(B);
-    p.C = static_cast<uint16_t *>(C);
-    return hip_status(atb::instance(g->instance).launch(p, static_cast<hipStream_t>(stream)));
+    if (g->b_format == ATB_FMT_BFP16) {
+        p.Bm = static_cast<const int8_t *>(B);
+        p.Be = static_cast<const uint8_t *>(B) + g->layout_b.exp_off;
+    } else {
+        p.B = static_cast<const uint16_t *>(B);
+    }
+    if (g->c_format == ATB_FMT_BFP16) {
+        p.Cm = static_cast<int8_t *>(C);
+        p.Ce = static_cast<uint8_t *>(C) + g->layout_c.exp_off;
+    } else {
+        p.C = static_cast<uint16_t *>(C);
+    }
+    const atb::Instance &x = atb::instance(g->instance);
+    if (g->b_format != ATB_FMT_BF16 || g->c_format != ATB_FMT_BF16)
+        return hip_status(x.launch_fmt(p, g->b_format, g->c_format, static_cast<hipStream_t>(stream)));
+    return hip_status(x.launch(p, static_cast<hipStream_t>(stream)));
 }
 
 extern "C" void atb_gemm_destroy(atb_gemm *g) { delete g; }

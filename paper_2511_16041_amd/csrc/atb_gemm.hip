@@ -74,6 +74,10 @@ struct Shape {
     static constexpr int A_BYTES = T_MA * PA;
     static constexpr int B_BYTES = T_K * PB;
     static constexpr int LDS_BYTES = AB * A_BYTES + 2 * B_BYTES;
+    // B given as BFP16 (B^T, N x K, blocks along K): the tile is staged like A, [n][k] with pitch PA
+    static constexpr int BT_BYTES = T_N * PA;
+    static constexpr int LDS_BYTES_BT = AB * A_BYTES + 2 * BT_BYTES;
+    static constexpr int BT_SLABS = T_N * T_K / 16 / NTS;      // 16-mantissa chunks of the tile per staging thread
     // staging work per thread: A in chunks of ACE mantissas (ACE/8 BFP16 blocks), B in chunks of 8 bf16
     static constexpr int ACE = (T_MA * T_K / NTS >= 16) ? 16 : 8;
     static constexpr int A_CHUNKS = T_MA * T_K / ACE;
@@ -111,7 +115,7 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // Buffer descriptors (V#) of the three inputs.  A load whose byte offset lies outside
 // [0, num_records) returns zero without touching memory, which is what masks the edges.
 struct Rsrc {
-    __amdgpu_buffer_rsrc_t am, ae, b;
+    __amdgpu_buffer_rsrc_t am, ae, b, bm, be;
 };
 
 constexpr int kRsrcFlags = 0x00020000;           // raw buffer, 32-bit data format
@@ -171,15 +175,29 @@ __device__ unsigned long long atb_trace_acc[16 * 8];
 // on alone, slowly).  There the staging work is split by kind instead of evenly: ROLE 1 (waves 0-3)
 // fetches, decodes and stores all of A, ROLE 2 (waves 4-7) requests all of B, which costs it a few
 // memory instructions and no arithmetic, so both waves of a SIMD reach the barrier together.
-template <class S, bool VEC, int ROLE>
+//
+// Storage formats (Sec. 6.1 lists the paper's precision configurations).  BBFP: B arrives as BFP16,
+// given as B^T (N x K, blocks along K, the same layout as A); its tile is fetched into registers,
+// decoded and stored to LDS as [n][k] like an A sub-tile -- by the second wave group, while the first
+// does the same for A -- and its fragments are plain 16-byte LDS reads.  Tile kt is fetched in the
+// first phase of K-step kt-3, decoded during K-step kt-2, read into fragment registers in the last
+// band of K-step kt-1.  CBFP: the epilogue quantises C to BFP16 in blocks of 8 along N.
+template <class S, bool VEC, int ROLE, bool BBFP = false, bool CBFP = false>
 struct TileKernel {
     static constexpr int NTS = S::NTS, ACE = S::ACE, A_CPR = S::A_CPR;
-    static constexpr int A_FIRST = (ROLE == 2) ? S::AO : 0;                              // first A slab of this wave group
-    static constexpr int APT = (ROLE == 0) ? S::A_SLABS : (ROLE == 1) ? S::AO : S::A_SLABS - S::AO;   // A chunks per thread per sub-tile
+    static constexpr int AO = BBFP ? S::A_SLABS : S::AO;                                 // with B in BFP16 the second group has its hands full
+    static constexpr int A_FIRST = (ROLE == 2) ? AO : 0;                                 // first A slab of this wave group
+    static constexpr int APT = (ROLE == 0) ? S::A_SLABS : (ROLE == 1) ? AO : S::A_SLABS - AO;   // A chunks per thread per sub-tile
     static constexpr int NPAIR = APT * ACE / 2;                                          // mantissa pairs per thread per sub-tile
     static constexpr int B_FIRST = (ROLE == 2) ? S::BO : 0;
-    static constexpr int BPT = (ROLE == 0) ? S::B_SLABS : (ROLE == 1) ? S::BO : S::B_SLABS - S::BO;   // B chunks per thread per tile
-    static constexpr int APTN = APT > 0 ? APT : 1, BPTN = BPT > 0 ? BPT : 1;             // array extents
+    static constexpr int BPT = BBFP ? 0 : (ROLE == 0) ? S::B_SLABS : (ROLE == 1) ? S::BO : S::B_SLABS - S::BO;   // bf16 B chunks per thread per tile
+    static constexpr int BTPT = !BBFP ? 0 : (ROLE == 1) ? 0 : S::BT_SLABS;               // BFP16 B chunks (16 mantissas) per thread per tile
+    static constexpr int NPAIR_B = BTPT * 8;                                             // B mantissa pairs per thread per tile
+    static constexpr int APTN = APT > 0 ? APT : 1, BPTN = BPT > 0 ? BPT : 1, BTPTN = BTPT > 0 ? BTPT : 1;   // array extents
+    static constexpr int B_BYTES = BBFP ? S::BT_BYTES : S::B_BYTES;
+    static_assert(!BBFP || (NPAIR_B % S::RHO == 0 && S::T_K % 16 == 0 && (S::T_N * S::T_K / 16) % NTS == 0), "BFP16 B staging must split evenly");
+    static_assert(!BBFP || S::LDS_BYTES_BT <= 160 * 1024, "LDS budget of a gfx950 CU");
+    static_assert(!BBFP || 2 * S::T_K <= 128, "two K-steps must stay inside the 128-byte row padding of both mantissa planes");
     static_assert((ROLE == 0) == (S::NT != 512), "two wave groups exactly when two waves share a SIMD");
 
     const GemmParams &p;
@@ -200,6 +218,15 @@ struct TileKernel {
     const uint16_t *b_ptr;             // start of the K-step the next B fetch belongs to
     int am_left, ae_left, b_left;      // bytes from those starts to the end of the planes
     int e_shift;                       // bit position of this thread's exponent byte(s) in the loaded dword
+    // B in BFP16: this thread's chunks of the B^T tile (row n, 16 mantissas), like the A members
+    char *bt_wr[2];
+    const char *bt_rd[2];
+    int bt_moff[BTPTN], bt_eoff[BTPTN];
+    const int8_t *bm_ptr;
+    const uint8_t *be_ptr;
+    int bm_left, be_left, eb_shift;
+    intx4 bt_mant[2][BTPTN];
+    unsigned bt_expo[2][BTPTN];
 
     floatx16 acc[S::MTW][S::NTW];
     bf16x8 bfrag[S::KS][S::NTW];       // this wave's slice of the resident B tile
@@ -236,7 +263,7 @@ struct TileKernel {
         }
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
-            char *b_base = lds + S::AB * S::A_BYTES + b * S::B_BYTES;
+            char *b_base = lds + S::AB * S::A_BYTES + b * B_BYTES;
             b_req[b] = b_base + slot0 * 16;
             b_wr[b] = b_req[b] + lane * 16;
             // B fragment through ds_read_b64_tr_b16: within each group of 16 lanes, lane i addresses
@@ -251,12 +278,38 @@ struct TileKernel {
         }
         am_ptr = p.Am;
         ae_ptr = p.Ae;
-        b_ptr = p.B;
         am_left = p.M * p.ldm;
         ae_left = p.M * p.lde;
-        b_left = p.K * p.N * 2;
         remake_a();
-        remake_b();
+        if constexpr (BBFP) {
+            // staging: thread -> (row n = stid / 4 + 64 i, chunk q = stid % 4 ... ) for T_K = 64; in general T_K / 16 chunks per row
+            constexpr int CPR = S::T_K / 16;
+            const int b_row = stid / CPR, b_q = stid % CPR;
+            eb_shift = ((b_q * 2) & 3) * 8;
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                char *b_base = lds + S::AB * S::A_BYTES + b * B_BYTES;
+                bt_wr[b] = b_base + b_row * S::PA + b_q * 32;
+                // B fragment: lane l reads column (row of B^T) l%32 of a band, k = ks*16 + 8*(l/32) .. +7
+                bt_rd[b] = b_base + (wn * S::NTW * 32 + (lane & 31)) * S::PA + (lane >> 5) * 16;
+            }
+            bm_ptr = p.Bm;
+            be_ptr = p.Be;
+            bm_left = p.N * p.ldbm;
+            be_left = p.N * p.ldbe;
+            remake_bt();
+            // rows >= N of B^T lie beyond the end of the planes and read as zero
+#pragma unroll
+            for (int i = 0; i < BTPT; ++i) {
+                const int grow = n0 + b_row + i * (NTS / CPR);
+                bt_moff[i] = grow * p.ldbm + b_q * 16;
+                bt_eoff[i] = grow * p.ldbe + ((b_q * 2) & ~3);
+            }
+        } else {
+            b_ptr = p.B;
+            b_left = p.K * p.N * 2;
+            remake_b();
+        }
         // Offsets of sub-tile 0 / K-step 0.  Rows >= M lie beyond the end of the planes and read as
         // zero; k never leaves a row because ldm is a multiple of 128 and of T_K (the mantissa bytes
         // between K and ldm are zero by the layout's contract).
@@ -304,6 +357,37 @@ struct TileKernel {
     }
 
     ATB_DEV void remake_b() { rs.b = make_rsrc(b_ptr, b_left); }
+
+    ATB_DEV void remake_bt()
+    {
+        rs.bm = make_rsrc(bm_ptr, bm_left);
+        rs.be = make_rsrc(be_ptr, be_left);
+    }
+
+    // Chunk i of the BFP16 B tile the B descriptors point at, into register set `set`; after the
+    // last chunk the descriptors move on to the next K-step.
+    template <int set, int i>
+    ATB_DEV void load_bt_chunk()
+    {
+        bt_mant[set][i] = __builtin_amdgcn_raw_buffer_load_b128(rs.bm, bt_moff[i], 0, 0);
+        bt_expo[set][i] = __builtin_amdgcn_raw_buffer_load_b32(rs.be, bt_eoff[i], 0, 0);
+        if constexpr (i == BTPT - 1) {
+            bm_ptr += S::T_K;
+            be_ptr += S::T_K / 8;
+            bm_left = max(bm_left - S::T_K, 0);
+            be_left = max(be_left - S::T_K / 8, 0);
+            remake_bt();
+        }
+    }
+
+    template <int set, int i = 0>
+    ATB_DEV void load_bt()
+    {
+        if constexpr (i < BTPT) {
+            load_bt_chunk<set, i>();
+            load_bt<set, i + 1>();
+        }
+    }
 
     // Chunk i of sub-tile `sub` of the K-step the A descriptors point at, into register set `set`.
     // After the last chunk of the last sub-tile the descriptors move on to the next K-step.
@@ -438,6 +522,32 @@ struct TileKernel {
         }
     }
 
+    // Same for pair t (0..7) of chunk i of the BFP16 B tile in register set `set`.
+    template <int set, int i, int t>
+    ATB_DEV void decode_bt_pair(char *b_dst)
+    {
+        if constexpr (t % 4 == 0) shift = (int)((bt_expo[set][i] >> (eb_shift + 8 * (t / 4))) & 0xFFu) - 133;
+        const int w = bt_mant[set][i][t / 2];
+        const float f0 = ldexpf(mant_to_float(w, (t % 2) * 2), shift);
+        const float f1 = ldexpf(mant_to_float(w, (t % 2) * 2 + 1), shift);
+        union { bf16x2 v; unsigned u; } pk;
+        pk.v = bf16x2{(__bf16)f0, (__bf16)f1};
+        dec[t % 4] = pk.u;
+        if constexpr (t % 4 == 3) {
+            char *dst = b_dst + i * (NTS / (S::T_K / 16)) * S::PA + (t / 4) * 16;
+            *reinterpret_cast<intx4 *>(dst) = intx4{(int)dec[0], (int)dec[1], (int)dec[2], (int)dec[3]};
+        }
+    }
+
+    template <int set, int j = 0>
+    ATB_DEV void store_bt_all(char *b_dst)
+    {
+        if constexpr (j < NPAIR_B) {
+            decode_bt_pair<set, j / 8, j % 8>(b_dst);
+            store_bt_all<set, j + 1>(b_dst);
+        }
+    }
+
     template <int i = 0>
     ATB_DEV void store_b_all(char *b_dst)
     {
@@ -448,24 +558,29 @@ struct TileKernel {
     }
 
     // ---- LDS -> registers ----------------------------------------------------------------
-    // B fragment (ks, nt): per lane l, column (wn*NTW + nt)*32 + l%32 and k = ks*16 + 8*(l/32) .. +7.
+    // B fragment (ks, nt) from LDS buffer `buf`: per lane l, column (wn*NTW + nt)*32 + l%32 and
+    // k = ks*16 + 8*(l/32) .. +7.
     template <int ks, int nt>
-    ATB_DEV void read_b_frag(const char *const (&b_src)[S::NBASE])
+    ATB_DEV void read_b_frag(int buf)
     {
-        const char *src = b_src[nt % S::NBASE] + ks * 16 * S::PB + (nt / S::NBASE) * (S::NBASE * 64);
-        typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
-        union { shortx4 s[2]; bf16x8 b; } u;
-        u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(src));
-        u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(src + 4 * S::PB));
-        bfrag[ks][nt] = u.b;
+        if constexpr (BBFP) {
+            bfrag[ks][nt] = *reinterpret_cast<const bf16x8 *>(bt_rd[buf] + nt * 32 * S::PA + ks * 32);
+        } else {
+            const char *src = b_rd[buf][nt % S::NBASE] + ks * 16 * S::PB + (nt / S::NBASE) * (S::NBASE * 64);
+            typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
+            union { shortx4 s[2]; bf16x8 b; } u;
+            u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(src));
+            u.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(src + 4 * S::PB));
+            bfrag[ks][nt] = u.b;
+        }
     }
 
     template <int f = 0>
-    ATB_DEV void read_b_frags_all(const char *const (&b_src)[S::NBASE])
+    ATB_DEV void read_b_frags_all(int buf)
     {
         if constexpr (f < S::KS * S::NTW) {
-            read_b_frag<f / S::NTW, f % S::NTW>(b_src);
-            read_b_frags_all<f + 1>(b_src);
+            read_b_frag<f / S::NTW, f % S::NTW>(buf);
+            read_b_frags_all<f + 1>(buf);
         }
     }
 
@@ -495,22 +610,28 @@ struct TileKernel {
     template <int s>
     static constexpr int n_side()
     {
-        return APT + (s == 0 ? BPT : 0) + NPAIR + ((!VEC && s + 1 == S::RHO) ? BPT : 0);
+        return APT + (s == 0 ? BPT + BTPT : 0) + NPAIR + NPAIR_B / S::RHO + ((!VEC && s + 1 == S::RHO) ? BPT : 0);
     }
 
     template <int kpar, int s, int j>
     ATB_DEV void side()
     {
         constexpr int g = kpar * S::RHO + s;
-        constexpr int n_la = APT, n_lb = (s == 0 ? BPT : 0);
-        if constexpr (j < n_lb) {
+        constexpr int n_la = APT, n_lb = (s == 0 ? BPT : 0), n_lt = (s == 0 ? BTPT : 0), n_dt = NPAIR_B / S::RHO;
+        constexpr int j1 = n_lb, j2 = j1 + n_lt, j3 = j2 + n_la, j4 = j3 + NPAIR, j5 = j4 + n_dt;
+        if constexpr (j < j1) {
             if constexpr (!(ATB_ABLATE & 512)) load_b_chunk<j>(kpar);
-        } else if constexpr (j < n_lb + n_la) {
-            if constexpr (!(ATB_ABLATE & 256)) load_a_chunk<g % S::PF, (s + S::PF) % S::RHO, j - n_lb>();
-        } else if constexpr (j < n_la + n_lb + NPAIR) {
-            decode_pair<(g + S::DA) % S::PF, (j - n_la - n_lb) / (ACE / 2), (j - n_la - n_lb) % (ACE / 2)>(a_wr[(g + S::DA) % S::AB]);
+        } else if constexpr (j < j2) {
+            load_bt_chunk<kpar ^ 1, j - j1>();
+        } else if constexpr (j < j3) {
+            if constexpr (!(ATB_ABLATE & 256)) load_a_chunk<g % S::PF, (s + S::PF) % S::RHO, j - j2>();
+        } else if constexpr (j < j4) {
+            decode_pair<(g + S::DA) % S::PF, (j - j3) / (ACE / 2), (j - j3) % (ACE / 2)>(a_wr[(g + S::DA) % S::AB]);
+        } else if constexpr (j < j5) {
+            constexpr int q = s * n_dt + (j - j4);
+            decode_bt_pair<kpar, q / 8, q % 8>(bt_wr[kpar]);
         } else {
-            store_b_chunk<j - n_la - n_lb - NPAIR>(b_wr[kpar]);
+            store_b_chunk<j - j5>(b_wr[kpar]);
         }
     }
 
@@ -555,7 +676,7 @@ struct TileKernel {
                 else if constexpr (S::AB == 4)      // first band of the next sub-tile, already complete in LDS
                     read_a_frag<par ^ 1, 0, ks>(a_rd[(g + 1) % S::AB]);
             }
-            if constexpr (last_phase && il + 1 == S::PER && !(ATB_ABLATE & 2)) read_b_frag<ks, nt>(b_rd[kpar ^ 1]);
+            if constexpr (last_phase && il + 1 == S::PER && !(ATB_ABLATE & 2)) read_b_frag<ks, nt>(kpar ^ 1);
             ATB_FENCE();
             slots<kpar, s, m + 1>();
         }
@@ -601,14 +722,22 @@ struct TileKernel {
         // prologue: B tiles 0 and 1 into LDS, the first PF A sub-tiles into registers, sub-tile 0
         // into LDS, B tile 0 into fragment registers
         load_b(0);
+        if constexpr (BBFP) { load_bt<0>(); load_bt<1>(); }
         prologue_loads();
         if constexpr (!VEC) store_b_all(b_wr[0]);
         load_b(1);
+        if constexpr (BBFP) {
+            // B tiles 0 and 1 decoded into LDS; tile 2 into the register set that K-step 0 decodes
+            store_bt_all<0>(bt_wr[0]);
+            store_bt_all<1>(bt_wr[1]);
+            load_bt<0>();
+        }
         store_a_all<0>(a_wr[0]);
         if constexpr (S::AB == 4) store_a_all<1>(a_wr[1]);
-        if constexpr (VEC) wait_vm<0>(); else store_b_all(b_wr[1]);
+        if constexpr (VEC && BPT > 0) wait_vm<0>();
+        if constexpr (!VEC) store_b_all(b_wr[1]);
         __syncthreads();
-        read_b_frags_all(b_rd[0]);
+        read_b_frags_all(0);
         // B buffer 0 is refilled from the first phase on: every wave must have its fragments first
         switch_barrier();
         if constexpr (S::AB == 4) read_first_band<0>(a_rd[0]);
@@ -625,7 +754,7 @@ struct TileKernel {
         // the requests for the two K-steps past the end (they read zeros) must not be in flight when
         // the next tile of this workgroup re-uses the registers and LDS buffers they target
         wait_vm<0>();
-        store_c();
+        if constexpr (CBFP) store_c_bfp(); else store_c();
     }
 
     // epilogue: fp32 -> bf16 (round to nearest even) and store, once per tile.  Lane l of band
@@ -661,6 +790,48 @@ struct TileKernel {
             }
         }
     }
+
+    // Epilogue for C in BFP16 (blocks of 8 along N): a block is the 4 consecutive columns of lane l
+    // plus the 4 of lane l ^ 32 (same row).  Same arithmetic as the stand-alone quantiser: shared
+    // exponent = largest fp32 exponent field, mantissa = clamp(rne(x * 2^(133 - E)), +-127).
+    // Needs N % 8 == 0; columns N .. ldcm - 1 (the row padding of the layout) are written as zero.
+    ATB_DEV void store_c_bfp()
+    {
+#pragma unroll
+        for (int a = 0; a < S::MTW; ++a) {
+            const int m = m0 + (a * S::WM + wm) * 32 + (lane & 31);
+#pragma unroll
+            for (int b = 0; b < S::NTW; ++b) {
+                const int nb = n0 + (wn * S::NTW + b) * 32 + 4 * (lane >> 5);
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int n = nb + 8 * g;
+                    const bool live = (n < p.N);           // whole blocks: N % 8 == 0
+                    float x[4];
+                    unsigned e = 0;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        x[t] = live ? acc[a][b][4 * g + t] : 0.0f;
+                        e = max(e, (__float_as_uint(x[t]) >> 23) & 0xFFu);
+                    }
+                    const unsigned other = (unsigned)__builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, (int)e);
+                    e = max(e, other);
+                    const int sh = 133 - (int)e;
+                    unsigned w = 0;
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        float r = rintf(ldexpf(x[t], sh));
+                        r = fminf(fmaxf(r, -127.0f), 127.0f);
+                        w |= ((unsigned)((int)r) & 0xFFu) << (8 * t);
+                    }
+                    if (m < p.M && n < p.ldcm) {
+                        *reinterpret_cast<unsigned *>(p.Cm + (int64_t)m * p.ldcm + n) = w;
+                        if ((lane >> 5) == 0) p.Ce[(int64_t)m * p.ldce + (n >> 3)] = (uint8_t)e;
+                    }
+                }
+            }
+        }
+    }
 };
 
 // Workgroup -> C tiles.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2); XCD x
@@ -670,7 +841,7 @@ struct TileKernel {
 // once, and workgroup b serves tiles b / 8, b / 8 + gridDim.x / 8, ... of its XCD's run.  The stores of one tile's epilogue
 // then drain while the next tile's first requests are already in flight, and no tile waits for a
 // workgroup launch.
-template <class S, bool VEC, int ROLE>
+template <class S, bool VEC, int ROLE, bool BBFP, bool CBFP>
 __device__ __forceinline__ void tile_loop(const GemmParams &p, char *lds)
 {
     const int total = p.tiles_m * p.tiles_n;
@@ -684,28 +855,28 @@ __device__ __forceinline__ void tile_loop(const GemmParams &p, char *lds)
         const int rows_here = min(p.group_m, p.tiles_m - band * p.group_m);
         const int tm = band * p.group_m + in_band % rows_here;
         const int tn = in_band / rows_here;
-        TileKernel<S, VEC, ROLE> tile(p, lds, tm * S::T_MC, tn * S::T_N);
+        TileKernel<S, VEC, ROLE, BBFP, CBFP> tile(p, lds, tm * S::T_MC, tn * S::T_N);
         tile.run();
     }
 }
 
-template <class S, bool VEC>
+template <class S, bool VEC, bool BBFP = false, bool CBFP = false>
 __global__ void __launch_bounds__(S::NT) atb_gemm_kernel(const GemmParams p)
 {
-    __shared__ __attribute__((aligned(16))) char lds[S::LDS_BYTES];
+    __shared__ __attribute__((aligned(16))) char lds[BBFP ? S::LDS_BYTES_BT : S::LDS_BYTES];
     if constexpr (S::NT == 512) {
         // wave-uniform branch; both sides execute the same sequence of barriers
         if (threadIdx.x < 256)
-            tile_loop<S, VEC, 1>(p, lds);
+            tile_loop<S, VEC, 1, BBFP, CBFP>(p, lds);
         else
-            tile_loop<S, VEC, 2>(p, lds);
+            tile_loop<S, VEC, 2, BBFP, CBFP>(p, lds);
     } else {
-        tile_loop<S, VEC, 0>(p, lds);
+        tile_loop<S, VEC, 0, BBFP, CBFP>(p, lds);
     }
 }
 
 // Workgroups of this kernel that one CU holds at a time (LDS- or register-limited), times the CUs.
-template <class S, bool VEC>
+template <class S, bool VEC, bool BBFP, bool CBFP>
 int resident_workgroups()
 {
     static int cached = 0;
@@ -713,7 +884,7 @@ int resident_workgroups()
         int dev = 0, cus = 0, per_cu = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, atb_gemm_kernel<S, VEC>, S::NT, 0) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, atb_gemm_kernel<S, VEC, BBFP, CBFP>, S::NT, 0) != hipSuccess ||
             cus < 8 || per_cu < 1)
             return 0;
         cached = cus * per_cu;
@@ -721,26 +892,40 @@ int resident_workgroups()
     return cached;
 }
 
-template <class S>
-hipError_t launch_instance(const GemmParams &p, hipStream_t stream)
+template <class S, bool VEC, bool BBFP, bool CBFP>
+hipError_t launch_kernel(const GemmParams &p, hipStream_t stream)
 {
     const int total = p.tiles_m * p.tiles_n;
     const int per_xcd = (total + 7) / 8;
-    const bool vec = (p.N % 8) == 0;
-    const int resident = vec ? resident_workgroups<S, true>() : resident_workgroups<S, false>();
+    const int resident = resident_workgroups<S, VEC, BBFP, CBFP>();
     if (resident == 0) return hipErrorInvalidDevice;
     // Small tiles keep one workgroup per tile: several of them share a CU and overlap each other's
     // prologue and epilogue already, and the hardware dispatcher balances them better than a fixed walk.
     constexpr bool persistent = S::T_MC * S::T_N >= 256 * 256;
     const int slots = persistent ? std::min(per_xcd, resident / 8) : per_xcd;     // workgroups per XCD
-    if (vec)
-        hipLaunchKernelGGL((atb_gemm_kernel<S, true>), dim3(slots * 8), dim3(S::NT), 0, stream, p);
-    else
-        hipLaunchKernelGGL((atb_gemm_kernel<S, false>), dim3(slots * 8), dim3(S::NT), 0, stream, p);
+    hipLaunchKernelGGL((atb_gemm_kernel<S, VEC, BBFP, CBFP>), dim3(slots * 8), dim3(S::NT), 0, stream, p);
     return hipGetLastError();
 }
 
 template <class S>
+hipError_t launch_instance(const GemmParams &p, hipStream_t stream)
+{
+    if ((p.N % 8) == 0) return launch_kernel<S, true, false, false>(p, stream);
+    return launch_kernel<S, false, false, false>(p, stream);
+}
+
+// The other storage formats (B and/or C in BFP16); they need N % 8 == 0 (checked by the caller).
+template <class S>
+hipError_t launch_instance_fmt(const GemmParams &p, int b_format, int c_format, hipStream_t stream)
+{
+    const bool bb = (b_format == ATB_FMT_BFP16), cb = (c_format == ATB_FMT_BFP16);
+    if (bb && cb) return launch_kernel<S, true, true, true>(p, stream);
+    if (bb) return launch_kernel<S, true, true, false>(p, stream);
+    if (cb) return launch_kernel<S, true, false, true>(p, stream);
+    return launch_kernel<S, true, false, false>(p, stream);
+}
+
+template <class S, bool FMT = false>
 Instance make_instance(double eff_scale = 1.0)
 {
     Instance i;
@@ -754,6 +939,7 @@ Instance make_instance(double eff_scale = 1.0)
     i.threads = S::NT;
     i.lds_bytes = S::LDS_BYTES;
     i.launch = &launch_instance<S>;
+    if constexpr (FMT) i.launch_fmt = &launch_instance_fmt<S>; else i.launch_fmt = nullptr;
     return i;
 }
 
@@ -765,9 +951,10 @@ const Instance g_instances[] = {
     // requests all of B, except at rho = 1, where a quarter of the (large) A tile goes to the second
     // group as well (measured on 8192^3: 1195 against 1164 TFLOP/s for the even split and 950 for 4 : 0).
     // The A fetch runs one to one and a half K-steps ahead of its use at every rho (PF phases).
-    make_instance<Shape<256, 256, 64, 256, 2, 4, 2, 2, 3, 0>>(),
-    make_instance<Shape<128, 256, 64, 256, 2, 4, 2, 2, 2, 0>>(),
-    make_instance<Shape<64, 256, 64, 256, 2, 4, 4, 2, 1, 0>>(),
+    // These three also come with B and/or C stored as BFP16 (the all-BFP16 configurations of Sec. 6.1).
+    make_instance<Shape<256, 256, 64, 256, 2, 4, 2, 2, 3, 0>, true>(),
+    make_instance<Shape<128, 256, 64, 256, 2, 4, 2, 2, 2, 0>, true>(),
+    make_instance<Shape<64, 256, 64, 256, 2, 4, 4, 2, 1, 0>, true>(),
     make_instance<Shape<32, 256, 64, 256, 1, 4, 8, 4>>(),
     // T_K = 128 exists only with ATB: at rho = 8 the A buffers take 17 KiB next to 128 KiB of B; the
     // symmetric tile would need 264 KiB of LDS (the "ATB makes an infeasible tile legal" case of Sec. 6.3)

@@ -13,10 +13,15 @@ namespace atb {
 struct GemmParams {
     const int8_t *Am;    // mantissa plane  [M][ldm]
     const uint8_t *Ae;   // exponent plane  [M][lde]
-    const uint16_t *B;   // bf16 [K][N]
-    uint16_t *C;         // bf16 [M][N]
+    const uint16_t *B;   // bf16 [K][N]                              (B in bf16)
+    uint16_t *C;         // bf16 [M][N]                              (C in bf16)
+    const int8_t *Bm;    // mantissa plane of B^T  [N][ldbm]         (B in BFP16, blocks along K)
+    const uint8_t *Be;   // exponent plane of B^T  [N][ldbe]
+    int8_t *Cm;          // mantissa plane of C    [M][ldcm]         (C in BFP16, blocks along N)
+    uint8_t *Ce;         // exponent plane of C    [M][ldce]
     int M, N, K;
     int ldm, lde;
+    int ldbm, ldbe, ldcm, ldce;
     int tiles_m, tiles_n;   // number of C tiles along M and N
     int group_m;            // tile rows that are walked together (rasterisation)
 };
@@ -29,6 +34,8 @@ struct Instance {
     int lds_bytes;          // static LDS of the kernel
     double eff_scale;       // measured microkernel efficiency of this instance relative to Eq. (12)'s fit
     hipError_t (*launch)(const GemmParams &p, hipStream_t stream);
+    // other storage formats (b_format, c_format as in atb_format); null where the instance has none
+    hipError_t (*launch_fmt)(const GemmParams &p, int b_format, int c_format, hipStream_t stream);
 };
 
 int instance_count();

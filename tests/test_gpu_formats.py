@@ -1,0 +1,122 @@
+"""B and/or C stored as BFP16 (the all-BFP16 precision configurations of the paper's
+Sec. 6.1, with fp32 accumulation) against the oracle, through the C ABI.
+
+B in BFP16 is handed over as B^T (N x K, blocks along K).  Its values are exact bf16 numbers, so the
+reference is the same fp64 GEMM on the decoded B.  C in BFP16 is the quantiser's rule applied to the
+accumulators: bit-exact against the oracle where fp32 accumulation is exact (small-integer inputs);
+otherwise the decoded C must lie within the GEMM tolerance plus half a mantissa step of its block,
+(2^-7 * sum|a||b| + 1e-6) + 2^(E - 134), E being the block's stored exponent."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2511_16041_amd as atb
+import workloads
+from helpers import bf16_tensor_bits, bits_to_bf16_tensor, pack_a_bfp, unpack_a_bfp
+
+pytestmark = pytest.mark.gpu
+
+FMT_TILES = [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256)]
+COMBOS = [("bfp16", "bf16"), ("bf16", "bfp16"), ("bfp16", "bfp16")]
+
+
+def _inputs(M, N, K, seed, exact):
+    """A fp32 [M][K], B^T fp32 [N][K] (both get quantised), seeded."""
+    if exact:
+        A, Bb = workloads.small_integer_inputs(M, N, K, seed=seed)
+        Bt = np.ascontiguousarray(oracle.bf16_to_double(Bb).T.astype(np.float32))
+    else:
+        A, Bb = workloads.make_inputs(workloads.CONFIGS["ragged"], M=M, N=N, K=K)
+        Bt = np.ascontiguousarray(oracle.bf16_to_double(Bb).T.astype(np.float32))
+    return A, Bt
+
+
+def _reference(A, Bt):
+    """(mant, expo, bmant, bexpo, B bits [K][N] of the BFP16-rounded B, C_ref bits, T, S)."""
+    mant, expo = oracle.quantize(A)
+    bmant, bexpo = oracle.quantize(Bt)
+    Bq_bits = np.ascontiguousarray(oracle.bfp16_as_bf16_bits(bmant, bexpo).T)
+    return mant, expo, bmant, bexpo, Bq_bits
+
+
+def _run(mant, expo, B_arg, M, N, K, tiles, b_format, c_format):
+    import torch
+    A_dev = torch.from_numpy(pack_a_bfp(mant, expo, atb.bfp16_layout(M, K))).cuda()
+    if b_format == "bfp16":
+        B_dev = torch.from_numpy(pack_a_bfp(B_arg[0], B_arg[1], atb.bfp16_layout(N, K))).cuda()
+    else:
+        B_dev = bits_to_bf16_tensor(B_arg, "cuda")
+    if c_format == "bfp16":
+        C_dev = torch.full((atb.bfp16_bytes(M, N),), 0xAB, dtype=torch.uint8, device="cuda")
+    else:
+        C_dev = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    g = atb.Gemm(M, N, K, *tiles, b_format=b_format, c_format=c_format)
+    out = g.run(A_dev, B_dev, C_dev)
+    torch.cuda.synchronize()
+    g.close()
+    if c_format == "bfp16":
+        cm, ce, pad = unpack_a_bfp(out.cpu().numpy(), M, N, atb.bfp16_layout(M, N))
+        return cm, ce, pad
+    return bf16_tensor_bits(out)
+
+
+@pytest.mark.parametrize("tiles", FMT_TILES)
+@pytest.mark.parametrize("fmt", COMBOS)
+def test_exact_inputs_bitwise(tiles, fmt):
+    b_format, c_format = fmt
+    M, N, K = 300, 264, 200
+    print(f"formats exact tiles={tiles} B={b_format} C={c_format}", flush=True)
+    A, Bt = _inputs(M, N, K, seed=7, exact=True)
+    mant, expo, bmant, bexpo, Bq_bits = _reference(A, Bt)
+    C_ref, _, S, _ = oracle.gemm(mant, expo, Bq_bits, want_sum=True)
+    B_arg = (bmant, bexpo) if b_format == "bfp16" else Bq_bits
+    got = _run(mant, expo, B_arg, M, N, K, tiles, b_format, c_format)
+    if c_format == "bfp16":
+        cm, ce, pad = got
+        rm, re_ = oracle.quantize(S.astype(np.float32))      # S is an exact small integer here
+        assert np.array_equal(ce, re_) and np.array_equal(cm, rm)
+        assert not pad.any(), "row padding of the C mantissa plane must be written as zero"
+    else:
+        assert np.array_equal(got, C_ref)
+
+
+@pytest.mark.parametrize("tiles", FMT_TILES)
+@pytest.mark.parametrize("fmt", COMBOS)
+@pytest.mark.parametrize("shape", [(520, 512, 136), (257, 264, 72), (33, 24, 8), (700, 1032, 320)])
+def test_random_inputs(tiles, fmt, shape):
+    b_format, c_format = fmt
+    M, N, K = shape
+    print(f"formats random {shape} tiles={tiles} B={b_format} C={c_format}", flush=True)
+    A, Bt = _inputs(M, N, K, seed=3, exact=False)
+    mant, expo, bmant, bexpo, Bq_bits = _reference(A, Bt)
+    C_ref, T, S, _ = oracle.gemm(mant, expo, Bq_bits, want_sum=True)
+    B_arg = (bmant, bexpo) if b_format == "bfp16" else Bq_bits
+    got = _run(mant, expo, B_arg, M, N, K, tiles, b_format, c_format)
+    tol = oracle.tolerance(T)
+    if c_format == "bfp16":
+        cm, ce, pad = got
+        val = oracle.decode(cm, ce)
+        step = np.repeat(np.ldexp(1.0, ce.astype(np.int64) - 134), 8, axis=1)     # half a mantissa step per block
+        err = np.abs(val - S)
+        bad = err > tol + step
+        assert not bad.any(), f"{bad.sum()} elements out of tolerance, worst {np.max(err / (tol + step)):.3g}"
+        # the stored exponent is the block maximum's: the largest mantissa of a non-zero block is at least 64
+        # unless the block's maximum sits right below a power of two and rounds up into the clamp
+        blockmax = np.abs(cm.astype(np.int32)).reshape(M, N // 8, 8).max(axis=2)
+        assert np.all((blockmax >= 64) | (ce == 0) | (blockmax == 0)), "exponent larger than the block needs"
+        assert not pad.any()
+    else:
+        err = np.abs(oracle.bf16_to_double(got) - oracle.bf16_to_double(C_ref))
+        assert not np.isnan(err).any()
+        assert not (err > tol).any(), f"worst ratio {np.max(err / tol):.3g}"
+
+
+def test_format_argument_errors():
+    # N not a multiple of 8
+    with pytest.raises(atb.AtbError) as e:
+        atb.Gemm(256, 260, 64, 128, 256, 64, 256, b_format="bfp16")
+    assert e.value.status == 1
+    # an instance that has no BFP16 B / C variant
+    with pytest.raises(atb.AtbError) as e:
+        atb.Gemm(256, 256, 64, 32, 256, 64, 256, c_format="bfp16")
+    assert e.value.status == 2

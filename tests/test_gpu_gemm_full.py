@@ -59,3 +59,40 @@ def test_full_size_sampled_rows(name, tile_list):
         assert not (err > tol).any(), f"{name} {tiles}: worst ratio {np.max(err / tol):.3g}"
         g.close()
         del C
+
+
+@pytest.mark.parametrize("name,tiles", [("square4096", (128, 256, 64, 256)), ("square8192", (128, 256, 64, 256)), ("square8192", (256, 256, 64, 256))])
+def test_full_size_all_bfp16_sampled_rows(name, tiles):
+    """A, B and C stored as BFP16 at full size: sampled rows of the decoded C against the oracle's
+    fp64 sums, within the GEMM tolerance plus half a mantissa step of the block."""
+    import torch
+    cfg = workloads.CONFIGS[name]
+    print(f"full-size all-BFP16 {name} {tiles}: generating", flush=True)
+    A, Bb = workloads.make_inputs(cfg)
+    M, K = A.shape
+    N = Bb.shape[1]
+    Bt = np.ascontiguousarray(oracle.bf16_to_double(Bb).T.astype(np.float32))
+    A_bfp = atb.bfp16_quantize(torch.from_numpy(A).cuda())
+    Bt_bfp = atb.bfp16_quantize(torch.from_numpy(Bt).cuda())
+    torch.cuda.synchronize()
+    mant, expo = oracle.quantize(A)
+    bmant, bexpo = oracle.quantize(Bt)
+    gm, ge, _ = unpack_a_bfp(Bt_bfp.cpu().numpy(), N, K, atb.bfp16_layout(N, K))
+    assert np.array_equal(gm, bmant) and np.array_equal(ge, bexpo)
+    del A, Bt, gm, ge
+    Bq_bits = np.ascontiguousarray(oracle.bfp16_as_bf16_bits(bmant, bexpo).T)
+    rows = _sample_rows(M, np.random.default_rng(2), n=24)
+    print(f"full-size all-BFP16 {name}: oracle gemm on {rows.size} rows", flush=True)
+    _, T, S, _ = oracle.gemm(mant, expo, Bq_bits, rows=rows, want_sum=True)
+    C = torch.full((atb.bfp16_bytes(M, N),), 0xAB, dtype=torch.uint8, device="cuda")
+    g = atb.Gemm(M, N, K, *tiles, b_format="bfp16", c_format="bfp16")
+    g.run(A_bfp, Bt_bfp, C)
+    torch.cuda.synchronize()
+    g.close()
+    cm, ce, pad = unpack_a_bfp(C.cpu().numpy(), M, N, atb.bfp16_layout(M, N))
+    assert not pad.any()
+    val = oracle.decode(cm[rows], ce[rows])
+    step = np.repeat(np.ldexp(1.0, ce[rows].astype(np.int64) - 134), 8, axis=1)
+    err = np.abs(val - S)
+    lim = oracle.tolerance(T) + step
+    assert not (err > lim).any(), f"worst ratio {np.max(err / lim):.3g}"
