@@ -143,6 +143,7 @@ def main():
         tiles = ranked[0].tiles()
     flop = 2.0 * M * N * K
 
+    raw_a = A_bfp.cpu().numpy() if not args.no_cpu else None
     plan = atb.Gemm(M, N, K, *tiles)
     info = plan.launch_info()
     wall, kernel_ms = time_plan(plan, A_bfp, B, C, args.steps, args.warmup)
@@ -215,10 +216,30 @@ def main():
         del Bt_bfp
         out["storage_formats"] = fmts
 
+    if not args.no_sweep and args.workload == "square8192":
+        # the problem sizes of the paper's Table 3 (N = 2048), each with the selector's pick
+        del A_bfp, B, C
+        scaling = []
+        for Mx in (1024, 2048, 4096):
+            for Kx in (2048, 4096, 8192):
+                Nx = 2048
+                Ax, Bx = workloads.make_inputs(cfg, M=Mx, N=Nx, K=Kx)
+                Ab = atb.bfp16_quantize(torch.from_numpy(Ax).cuda())
+                Bd = torch.from_numpy(Bx.view(np.int16)).view(torch.bfloat16).cuda()
+                Cd = torch.empty((Mx, Nx), dtype=torch.bfloat16, device="cuda")
+                pick = atb.select_tiles(Mx, Nx, Kx)[0]
+                p = atb.Gemm(Mx, Nx, Kx, *pick.tiles())
+                _, kms = time_plan(p, Ab, Bd, Cd, 50, 10)
+                p.close()
+                scaling.append({"M": Mx, "K": Kx, "N": Nx, "tiles": list(pick.tiles()),
+                                "tflops": round(2.0 * Mx * Nx * Kx / (kms * 1e-3) / 1e12, 1),
+                                "model_tflops": round(pick.pred_flops / 1e12, 1)})
+        out["table3_shapes"] = scaling
+
     if not args.no_cpu:
         import oracle
         lay = atb.bfp16_layout(M, K)
-        raw = A_bfp.cpu().numpy()
+        raw = raw_a
         nrows = min(args.cpu_rows, M)
         mant = raw[: M * lay.ldm].reshape(M, lay.ldm)[:nrows, :K].view(np.int8).copy()
         expo = raw[lay.exp_off: lay.exp_off + M * lay.lde].reshape(M, lay.lde)[:nrows, : K // 8].copy()

@@ -44,10 +44,11 @@ typedef short shortx4 __attribute__((ext_vector_type(4)));
 // Sign-extended byte `byte` of word w as float (one v_cvt_f32_i32 with a byte select).
 ATB_DEV float mant_to_float(int w, int byte) { return (float)(int)(signed char)(w >> (8 * byte)); }
 
-template <int T_MA_, int T_MC_, int T_K_, int T_N_, int WM_, int WN_, int PF_, int AB_ = 2, int AO_ = -1, int BO_ = 0>
+template <int T_MA_, int T_MC_, int T_K_, int T_N_, int WM_, int WN_, int PF_, int AB_ = 2, int AO_ = -1, int BO_ = 0, int KU_ = 2>
 struct Shape {
     static constexpr int T_MA = T_MA_, T_MC = T_MC_, T_K = T_K_, T_N = T_N_, WM = WM_, WN = WN_;
     static constexpr int PF = PF_;                // A sub-tiles fetched this many phases ahead of their use
+    static constexpr int KU = KU_;                // K-steps per iteration of the (unrolled) K loop: every buffer and register-set index is static
     // A LDS buffers.  2: sub-tile g+1 is decoded while sub-tile g is multiplied, and each microkernel
     // starts by reading its first fragments after the switch barrier.  4: the small A sub-tiles of
     // ATB leave room for a deeper ring: sub-tile g+2 is decoded while g is multiplied, so sub-tile
@@ -95,8 +96,8 @@ struct Shape {
     static constexpr int SWZ = (T_N / 8 >= 16) ? 2 : 1;
     static constexpr int NBASE = (NTW < 4) ? NTW : 4;   // distinct per-lane read bases (the swizzle permutes 4 bands)
     static_assert(T_MC % T_MA == 0, "rho must be an integer");
-    static_assert(PF >= 2 && (2 * RHO) % PF == 0, "prefetch distance: at least 2 (fetch and decode overlap), dividing two K-steps of sub-tiles");
-    static_assert(AB == 2 || (AB == 4 && PF >= 3 && (2 * RHO) % 4 == 0), "4 A buffers need rho >= 2 and a fetch distance of 3 or more");
+    static_assert(KU % 2 == 0 && PF >= 2 && (KU * RHO) % PF == 0, "prefetch distance: at least 2 (fetch and decode overlap), dividing the sub-tiles of one loop iteration");
+    static_assert(AB == 2 || (AB == 4 && PF >= 3 && (KU * RHO) % 4 == 0), "4 A buffers need a fetch distance of 3 or more and must divide the sub-tiles of one loop iteration");
     static_assert(128 % T_K == 0 && T_K % 32 == 0, "T_K must divide the 128-byte row padding of the mantissa plane; exponent dwords stay aligned");
     static_assert(T_MA % 32 == 0 && T_N % (32 * WN) == 0 && T_K % 16 == 0, "MFMA 32x32x16 granularity");
     static_assert(MT % WM == 0 && SMT % WM == 0, "every sub-tile must feed every wave row equally");
@@ -197,7 +198,7 @@ struct TileKernel {
     static constexpr int B_BYTES = BBFP ? S::BT_BYTES : S::B_BYTES;
     static_assert(!BBFP || (NPAIR_B % S::RHO == 0 && S::T_K % 16 == 0 && (S::T_N * S::T_K / 16) % NTS == 0), "BFP16 B staging must split evenly");
     static_assert(!BBFP || S::LDS_BYTES_BT <= 160 * 1024, "LDS budget of a gfx950 CU");
-    static_assert(!BBFP || 2 * S::T_K <= 128, "two K-steps must stay inside the 128-byte row padding of both mantissa planes");
+    static_assert(!BBFP || S::KU * S::T_K <= 128, "a loop body of K-steps must stay inside the 128-byte row padding of both mantissa planes");
     static_assert((ROLE == 0) == (S::NT != 512), "two wave groups exactly when two waves share a SIMD");
 
     const GemmParams &p;
@@ -613,10 +614,11 @@ struct TileKernel {
         return APT + (s == 0 ? BPT + BTPT : 0) + NPAIR + NPAIR_B / S::RHO + ((!VEC && s + 1 == S::RHO) ? BPT : 0);
     }
 
-    template <int kpar, int s, int j>
+    template <int ki, int s, int j>
     ATB_DEV void side()
     {
-        constexpr int g = kpar * S::RHO + s;
+        constexpr int kpar = ki & 1;             // parity of the K-step: B buffers and B register sets
+        constexpr int g = ki * S::RHO + s;       // running sub-tile index within the loop body
         constexpr int n_la = APT, n_lb = (s == 0 ? BPT : 0), n_lt = (s == 0 ? BTPT : 0), n_dt = NPAIR_B / S::RHO;
         constexpr int j1 = n_lb, j2 = j1 + n_lt, j3 = j2 + n_la, j4 = j3 + NPAIR, j5 = j4 + n_dt;
         if constexpr (j < j1) {
@@ -635,12 +637,12 @@ struct TileKernel {
         }
     }
 
-    template <int kpar, int s, int j, int jend>
+    template <int ki, int s, int j, int jend>
     ATB_DEV void side_range()
     {
         if constexpr (j < jend) {
-            side<kpar, s, j>();
-            side_range<kpar, s, j + 1, jend>();
+            side<ki, s, j>();
+            side_range<ki, s, j + 1, jend>();
         }
     }
 
@@ -648,15 +650,16 @@ struct TileKernel {
     // the A fragment of the same k-slice of the next band; in the last band of the K-step the B
     // fragment just used is replaced by the next K-step's.  The fences pin this order, so that the
     // VALU decode and the LDS traffic issue in the shadow of the 8-pass MFMA.
-    template <int kpar, int s, int m>
+    template <int ki, int s, int m>
     ATB_DEV void slots()
     {
         if constexpr (m < S::NM) {
+            constexpr int kpar = ki & 1;
             constexpr int il = m / (S::KS * S::NTW), ks = (m / S::NTW) % S::KS, nt = m % S::NTW;
             constexpr int local = (s * S::SMT) / S::WM + il;      // accumulator band of this wave
             constexpr bool last_phase = (s + 1 == S::RHO);
             constexpr int nside = n_side<s>();
-            constexpr int g = kpar * S::RHO + s;
+            constexpr int g = ki * S::RHO + s;
             constexpr int par = (g * S::PER + il) % 2;            // which half of afrag this band uses
             if constexpr (!(ATB_ABLATE & 32))
                 acc[local][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag[ks][nt], afrag[par][ks],
@@ -669,7 +672,7 @@ struct TileKernel {
             constexpr int NS = S::NM - S::NM / 8;
             constexpr int j0 = (m * nside) / NS < nside ? (m * nside) / NS : nside;
             constexpr int j1 = ((m + 1) * nside) / NS < nside ? ((m + 1) * nside) / NS : nside;
-            side_range<kpar, s, j0, j1>();
+            side_range<ki, s, j0, j1>();
             if constexpr (nt == S::NTW - 1 && !(ATB_ABLATE & 16)) {
                 if constexpr (il + 1 < S::PER)
                     read_a_frag<par ^ 1, il + 1, ks>(a_rd[g % S::AB]);
@@ -678,20 +681,20 @@ struct TileKernel {
             }
             if constexpr (last_phase && il + 1 == S::PER && !(ATB_ABLATE & 2)) read_b_frag<ks, nt>(kpar ^ 1);
             ATB_FENCE();
-            slots<kpar, s, m + 1>();
+            slots<ki, s, m + 1>();
         }
     }
 
-    // Phase s of a K-step of parity kpar.
-    template <int kpar, int s>
+    // Phase s of K-step ki of the loop body.
+    template <int ki, int s>
     ATB_DEV void phases()
     {
         if constexpr (s < S::RHO) {
-            constexpr int g = kpar * S::RHO + s;
+            constexpr int g = ki * S::RHO + s;
             if constexpr (S::AB == 2) read_first_band<(g * S::PER) % 2>(a_rd[g % 2]);
             ATB_FENCE();
             ATB_STAMP(1);
-            slots<kpar, s, 0>();
+            slots<ki, s, 0>();
             ATB_STAMP(2);
             // The B tile requested (straight into LDS) in the first phase of a K-step is read in the
             // last band of the next K-step, so the last barrier before that band has to publish it.
@@ -704,7 +707,16 @@ struct TileKernel {
                 wait_vm<(2 * S::RHO - 1) * APT * 2 + BPT>();
             if constexpr (!(ATB_ABLATE & 64)) switch_barrier();   // the "kernel switch" of the ATB nest
             ATB_STAMP(3);
-            phases<kpar, s + 1>();
+            phases<ki, s + 1>();
+        }
+    }
+
+    template <int ki>
+    ATB_DEV void ksteps()
+    {
+        if constexpr (ki < S::KU) {
+            phases<ki, 0>();
+            ksteps<ki + 1>();
         }
     }
 
@@ -742,14 +754,11 @@ struct TileKernel {
         switch_barrier();
         if constexpr (S::AB == 4) read_first_band<0>(a_rd[0]);
 
-        // an odd number of K-steps is rounded up: the extra step multiplies by B rows >= K, which
-        // read as zero
+        // the number of K-steps is rounded up to a whole loop body: the extra steps multiply by
+        // B rows >= K, which read as zero
         const int KT = (p.K + S::T_K - 1) / S::T_K;
         ATB_STAMP(0);
-        for (int kt = 0; kt < KT; kt += 2) {
-            phases<0, 0>();
-            phases<1, 0>();
-        }
+        for (int kt = 0; kt < KT; kt += S::KU) ksteps<0>();
         ATB_TRACE_FLUSH();
         // the requests for the two K-steps past the end (they read zeros) must not be in flight when
         // the next tile of this workgroup re-uses the registers and LDS buffers they target
@@ -938,6 +947,7 @@ Instance make_instance(double eff_scale = 1.0)
     i.wave_n = S::WN;
     i.threads = S::NT;
     i.lds_bytes = S::LDS_BYTES;
+    i.wg_per_cu = std::max(1, std::min(8, (160 * 1024) / S::LDS_BYTES));   // LDS-limited in every instance
     i.launch = &launch_instance<S>;
     if constexpr (FMT) i.launch_fmt = &launch_instance_fmt<S>; else i.launch_fmt = nullptr;
     return i;
@@ -959,9 +969,18 @@ const Instance g_instances[] = {
     // T_K = 128 exists only with ATB: at rho = 8 the A buffers take 17 KiB next to 128 KiB of B; the
     // symmetric tile would need 264 KiB of LDS (the "ATB makes an infeasible tile legal" case of Sec. 6.3)
     make_instance<Shape<32, 256, 128, 256, 1, 4, 8, 2>>(0.96),   // measured against the fit, which is dominated by the 2 x 4 grid instances
+    // mid-size tiles for problems with too few 256 x 256 tiles to fill 256 CUs (e.g. the N = 2048
+    // shapes of the paper's Table 3): 128 x 256 on 8 waves, 128 x 128 on 4 waves (two workgroups per CU)
+    // (the factors are measured full-load throughput over the 256 x 256 family's fit: workgroups that
+    // share a CU overlap each other's barriers and latencies, which the per-tile formula does not see;
+    // the symmetric 128 x 256 tile has a single barrier per short K-step and waits for its B tile there)
+    make_instance<Shape<128, 128, 64, 256, 2, 4, 2, 2>>(0.50),
+    make_instance<Shape<64, 128, 64, 256, 2, 4, 4, 2>>(0.92),
+    make_instance<Shape<128, 128, 64, 128, 2, 2, 2, 2>>(1.07),
+    make_instance<Shape<64, 128, 64, 128, 2, 2, 4, 2>>(1.16),
     // small tiles for small problems
-    make_instance<Shape<64, 64, 64, 64, 2, 2, 2, 2>>(),
-    make_instance<Shape<32, 64, 64, 64, 1, 2, 2, 2>>(),
+    make_instance<Shape<64, 64, 64, 64, 2, 2, 2, 2>>(1.47),
+    make_instance<Shape<32, 64, 64, 64, 1, 2, 2, 2>>(1.33),
 };
 
 

@@ -32,6 +32,7 @@ struct Instance {
     int wave_m, wave_n;     // wave grid inside the workgroup
     int threads;            // wave_m * wave_n * 64
     int lds_bytes;          // static LDS of the kernel
+    int wg_per_cu;          // workgroups of this instance that share a CU
     double eff_scale;       // measured microkernel efficiency of this instance relative to Eq. (12)'s fit
     hipError_t (*launch)(const GemmParams &p, hipStream_t stream);
     // other storage formats (b_format, c_format as in atb_format); null where the instance has none

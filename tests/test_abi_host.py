@@ -147,3 +147,34 @@ def test_model_mi355x_mode_and_selector():
     small = atb.select_tiles(256, 256, 256)
     assert small[0].T_MC == 64                        # 16 small tiles beat one big tile on 256 CUs
     assert atb.lib().atb_select_tiles(0, 1, 8, None, None, 0, None) == 1
+
+
+def test_create_fmt_validation():
+    """Plans with B and/or C stored as BFP16: argument checks run on the host."""
+    L = atb.lib()
+    h = ctypes.c_void_p()
+
+    def create(M, N, K, t, bf, cf):
+        return L.atb_gemm_create_fmt(ctypes.byref(h), M, N, K, *t, bf, cf)
+
+    assert create(512, 512, 256, (128, 256, 64, 256), 1, 1) == 0 and h.value
+    L.atb_gemm_destroy(h)
+    assert create(512, 512, 256, (128, 256, 64, 256), 0, 0) == 0 and h.value      # same as atb_gemm_create
+    L.atb_gemm_destroy(h)
+    assert create(512, 508, 256, (128, 256, 64, 256), 1, 0) == 1 and not h.value  # N % 8 != 0
+    assert create(512, 512, 256, (128, 256, 64, 256), 2, 0) == 1                  # unknown format
+    assert create(512, 512, 256, (32, 256, 64, 256), 0, 1) == 2                   # instance without format variants
+    assert create(512, 512, 256, (64, 64, 64, 64), 1, 1) == 2
+
+
+def test_selector_tracks_problem_size():
+    """Few C tiles: smaller tiles fill the chip better (the N = 2048 shapes of the paper's Table 3)."""
+    assert atb.select_tiles(8192, 8192, 8192)[0].T_MC == 256
+    assert atb.select_tiles(4096, 2048, 4096)[0].tiles()[1:] == (128, 64, 256)
+    assert atb.select_tiles(1024, 2048, 4096)[0].T_MC <= 128
+    assert atb.select_tiles(1024, 2048, 4096)[0].T_N <= 128
+    # a launch never beats its fixed cost, and predictions grow with the problem
+    a = atb.select_tiles(256, 256, 256)[0].pred_flops
+    b = atb.select_tiles(1024, 1024, 1024)[0].pred_flops
+    c = atb.select_tiles(8192, 8192, 8192)[0].pred_flops
+    assert a < b < c and a < 2.0 * 256 ** 3 / 6e-6

@@ -15,6 +15,7 @@ pytestmark = pytest.mark.gpu
 BIG = [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256), (32, 256, 64, 256)]
 WIDE_K = [(32, 256, 128, 256)]      # T_K = 128: feasible only with ATB
 SMALL = [(64, 64, 64, 64), (32, 64, 64, 64)]
+MID = [(128, 128, 64, 256), (64, 128, 64, 256), (128, 128, 64, 128), (64, 128, 64, 128)]
 
 
 def _run(mant, expo, Bb, tiles, poison=True):
@@ -43,10 +44,10 @@ def _check(Cg_bits, C_ref, T, what):
 
 
 def test_instances_cover_the_tests():
-    assert set(BIG + SMALL + WIDE_K) == set(atb.instances())
+    assert set(BIG + SMALL + MID + WIDE_K) == set(atb.instances())
 
 
-@pytest.mark.parametrize("tiles", SMALL + BIG + WIDE_K)
+@pytest.mark.parametrize("tiles", SMALL + MID + BIG + WIDE_K)
 def test_small256_config(tiles):
     print(f"gemm small256 tiles={tiles}", flush=True)
     A, Bb = workloads.make_inputs(workloads.CONFIGS["small256"])
@@ -55,7 +56,7 @@ def test_small256_config(tiles):
     _check(_run(mant, expo, Bb, tiles), C_ref, T, f"small256 {tiles}")
 
 
-@pytest.mark.parametrize("tiles", SMALL + BIG + WIDE_K)
+@pytest.mark.parametrize("tiles", SMALL + MID + BIG + WIDE_K)
 @pytest.mark.parametrize("shape", [(300, 500, 264), (257, 263, 72), (33, 20, 8), (1, 1, 8), (520, 516, 136), (300, 499, 64)])
 def test_ragged_shapes(tiles, shape):
     """Several tiles plus ragged M and N tails, a K tail of 8, N not a multiple of 8 or of 4."""
@@ -67,7 +68,7 @@ def test_ragged_shapes(tiles, shape):
     _check(_run(mant, expo, Bb, tiles), C_ref, T, f"ragged {shape} {tiles}")
 
 
-@pytest.mark.parametrize("tiles", SMALL + BIG + WIDE_K)
+@pytest.mark.parametrize("tiles", SMALL + MID + BIG + WIDE_K)
 def test_exact_inputs_bitwise(tiles):
     """Small-integer inputs: fp32 accumulation is exact in any order, so every instance
     (every rho) must equal the oracle bit for bit."""
