@@ -202,10 +202,59 @@ atb_status atb_model_eval(int64_t M, int64_t N, int64_t K, int T_MA, int T_MC, i
 
 /* Rank the compiled instances for a problem by predicted throughput
  * (infeasible ones last): atb_model_eval's prediction, with the compute bound
- * scaled by the measured microkernel factor an instance may carry.  Writes min(capacity, count) entries to `ranked`
+ * scaled by the measured full-load factor an instance may carry, rounds of
+ * tiles counted in workgroups resident per CU, partly filled rounds credited
+ * with the clock the idle CUs leave, and a fixed launch cost.  Writes min(capacity, count) entries to `ranked`
  * (HOST) and the number of instances to *count.  ranked[0] is the pick. */
 atb_status atb_select_tiles(int64_t M, int64_t N, int64_t K, const atb_hw_params *hw,
                             atb_choice *ranked, int capacity, int *count);
+
+/* ------------------------------------------------- microkernel issue model */
+
+/* Sec. 4 of the paper models its microkernel on a VLIW core: a prolog bounded
+ * by load latency and load-unit throughput (Eq. 4), a steady state whose
+ * initiation interval is the larger of the MAC pipeline constraint and the
+ * load constraint (Eq. 5), an epilog (Eq. 8), and their sum per kernel call
+ * (Eq. 9), overlapped when several accumulation clusters are in flight
+ * (Eq. 10).  This is the same decomposition for one gfx950 CU, with unit costs
+ * measured on MI355X (csrc/microbench/unit_costs.hip): per C tile and K-step,
+ * in shader-clock cycles,
+ *   mfma   = n_mfma * 32 / 4                    matrix pipes (8-pass MFMA, 4 SIMDs)
+ *   valu   = (n_mfma * 17 + n_decode * 6.5 + n_addr * 4) / 4
+ *                                               VALU issue ports: an MFMA blocks its SIMD's port for
+ *                                               17 of its 32 cycles; a decode instruction costs 6.5
+ *   lds    = 4.7 n_b128_reads + 4.6 n_tr_reads + bytes_written / 76
+ *   vmem   = bytes_requested / 64
+ *   steady = max of the four / 0.85             (II; 0.85 = co-issue efficiency, one global constant)
+ *   switch = (120 + 4.7 * first-band reads + 150) / waves per SIMD
+ *                                               prolog (LDS latency, Eq. 4 form) + epilog (barrier)
+ *   kstep  = steady + rho * switch              (Eq. 9; workgroups sharing a CU overlap, Eq. 10)
+ * mfma_util = mfma / kstep; the chip is power-limited under this kernel, the
+ * measured clock follows 1.248 GHz * mfma_util^-0.6 (capped at 2.4), and
+ * pred_flops = flop per K-step * CUs / (kstep / clock).
+ * Predicts the full-load throughput of the compiled instances within 15 %
+ * from the tile factors and the wave grid alone (tests/golden/mi355x_instances.txt);
+ * it does not see pipeline stalls of a particular schedule. */
+typedef struct atb_micro_model {
+    double n_mfma;         /* MFMAs per C tile and K-step */
+    double mfma_cycles, valu_cycles, lds_cycles, vmem_cycles;
+    double steady_cycles;  /* II of one K-step */
+    double switch_cycles;  /* prolog + epilog of one microkernel call */
+    double kstep_cycles;
+    double mfma_util;      /* predicted share of cycles the matrix pipes are busy */
+    double clock_hz;       /* predicted shader clock under that load */
+    double pred_flops;     /* whole chip, full load */
+} atb_micro_model;
+
+/* wave_m x wave_n: the wave grid of the workgroup (64-lane waves); wg_per_cu:
+ * workgroups that share a CU.  ATB_ERR_INVALID_ARG / ATB_ERR_BAD_TILE if the
+ * factors do not divide (32-row bands per wave row, 32-column bands per wave
+ * column, T_K % 16). */
+atb_status atb_model_microkernel(int T_MA, int T_MC, int T_K, int T_N, int wave_m, int wave_n,
+                                 int wg_per_cu, atb_micro_model *out);
+
+/* Wave grid and residency of compiled instance `index` (inputs of the call above). */
+atb_status atb_instance_geometry(int index, int *wave_m, int *wave_n, int *wg_per_cu);
 
 #ifdef __cplusplus
 }

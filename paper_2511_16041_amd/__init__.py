@@ -50,6 +50,12 @@ class Choice(ctypes.Structure):
         return (self.T_MA, self.T_MC, self.T_K, self.T_N)
 
 
+class MicroModel(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_double) for n in ("n_mfma", "mfma_cycles", "valu_cycles", "lds_cycles", "vmem_cycles",
+                                               "steady_cycles", "switch_cycles", "kstep_cycles", "mfma_util",
+                                               "clock_hz", "pred_flops")]
+
+
 class Bfp16Layout(ctypes.Structure):
     _fields_ = [("ldm", ctypes.c_int64), ("lde", ctypes.c_int64),
                 ("exp_off", ctypes.c_int64), ("bytes", ctypes.c_int64)]
@@ -60,7 +66,7 @@ EXPORTS = [
     "atb_status_string", "atb_last_hip_error", "atb_gemm_create", "atb_gemm_create_fmt", "atb_gemm_run", "atb_gemm_destroy",
     "atb_gemm_launch_info", "atb_instance_count", "atb_instance_get", "atb_bfp16_layout", "atb_bfp16_bytes",
     "atb_bfp16_quantize", "atb_bfp16_decode", "atb_hw_params_xdna2", "atb_hw_params_mi355x",
-    "atb_model_eval", "atb_select_tiles",
+    "atb_model_eval", "atb_select_tiles", "atb_model_microkernel", "atb_instance_geometry",
 ]
 
 
@@ -105,6 +111,10 @@ def lib() -> ctypes.CDLL:
     L.atb_model_eval.argtypes = [i64, i64, i64, ci, ci, ci, ci, ctypes.POINTER(HwParams), ctypes.POINTER(Choice)]
     L.atb_select_tiles.restype = ci
     L.atb_select_tiles.argtypes = [i64, i64, i64, ctypes.POINTER(HwParams), ctypes.POINTER(Choice), ci, pi]
+    L.atb_model_microkernel.restype = ci
+    L.atb_model_microkernel.argtypes = [ci, ci, ci, ci, ci, ci, ci, ctypes.POINTER(MicroModel)]
+    L.atb_instance_geometry.restype = ci
+    L.atb_instance_geometry.argtypes = [ci, pi, pi, pi]
     _lib = L
     return L
 
@@ -155,6 +165,19 @@ def model_eval(M: int, N: int, K: int, T_MA: int, T_MC: int, T_K: int, T_N: int,
     _check(lib().atb_model_eval(M, N, K, T_MA, T_MC, T_K, T_N,
                                 ctypes.byref(hw) if hw is not None else None, ctypes.byref(ch)), "atb_model_eval")
     return ch
+
+
+def instance_geometry(index: int) -> Tuple[int, int, int]:
+    a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    _check(lib().atb_instance_geometry(index, a, b, c), "atb_instance_geometry")
+    return a.value, b.value, c.value
+
+
+def model_microkernel(T_MA: int, T_MC: int, T_K: int, T_N: int, wave_m: int, wave_n: int, wg_per_cu: int) -> MicroModel:
+    m = MicroModel()
+    _check(lib().atb_model_microkernel(T_MA, T_MC, T_K, T_N, wave_m, wave_n, wg_per_cu, ctypes.byref(m)),
+           "atb_model_microkernel")
+    return m
 
 
 def select_tiles(M: int, N: int, K: int, hw: Optional[HwParams] = None) -> List[Choice]:

@@ -45,6 +45,19 @@ def build(verbose: bool = False, extra=()) -> str:
     return OUT
 
 
+def build_microbench(verbose: bool = False) -> str:
+    """The unit-cost micro-benchmark behind the constants of atb_model_microkernel (a developer
+    tool, a stand-alone executable; nothing loads it)."""
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    exe = os.path.join(OBJ_DIR, "unit_costs")
+    cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Wno-unused-command-line-argument", "-o", exe, os.path.join(CSRC, "microbench", "unit_costs.hip")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return exe
+
+
 def ensure_built() -> str:
     # Build only when nothing is built; after editing a source, run this file again.
     if not os.path.exists(OUT):
@@ -55,3 +68,4 @@ def ensure_built() -> str:
 if __name__ == "__main__":
     extra = [a for a in sys.argv[1:]]
     print(build(verbose=True, extra=extra))
+    print(build_microbench(verbose=True))

@@ -186,3 +186,48 @@ extern "C" atb_status atb_select_tiles(int64_t M, int64_t N, int64_t K, const at
     for (int i = 0; i < capacity && i < (int)all.size(); ++i) ranked[i] = all[i];
     return ATB_OK;
 }
+
+extern "C" atb_status atb_model_microkernel(int T_MA, int T_MC, int T_K, int T_N, int wave_m, int wave_n,
+                                            int wg_per_cu, atb_micro_model *out)
+{
+    if (!out || T_MA < 1 || T_MC < 1 || T_K < 1 || T_N < 1 || wave_m < 1 || wave_n < 1 || wg_per_cu < 1)
+        return ATB_ERR_INVALID_ARG;
+    if (T_MC % T_MA != 0 || T_K % 16 != 0 || T_MC % (32 * wave_m) != 0 || T_N % (32 * wave_n) != 0) return ATB_ERR_BAD_TILE;
+    // unit costs, shader-clock cycles (measured, see the header)
+    const double kMfmaPipe = 32.0, kMfmaPort = 17.0, kDecodeValu = 6.5, kAddrValu = 4.0;
+    const double kReadB128 = 4.7, kReadTr = 4.6, kWriteBytesPerClk = 76.0, kVmemBytesPerClk = 64.0;
+    const double kLdsLatency = 120.0, kBarrier = 150.0, kCoIssue = 0.85;
+    const double waves = (double)wave_m * wave_n, ks = T_K / 16.0;
+    const double mtw = T_MC / 32.0 / wave_m, ntw = T_N / 32.0 / wave_n, rho = (double)T_MC / T_MA;
+
+    atb_micro_model m;
+    std::memset(&m, 0, sizeof m);
+    m.n_mfma = (double)T_MC * T_N * T_K / (32.0 * 32.0 * 16.0);
+    m.mfma_cycles = m.n_mfma * kMfmaPipe / 4.0;
+    const double n_decode = 2.5 * T_MC * T_K / 64.0;            // wave instructions: 5 per 2 mantissas per lane
+    const double n_addr = 17.0 * waves;                          // descriptor advance, exponent extraction
+    m.valu_cycles = (m.n_mfma * kMfmaPort + n_decode * kDecodeValu + n_addr * kAddrValu) / 4.0;
+    const double a_reads = waves * mtw * ks;                     // every wave reads its bands' fragments once
+    const double b_reads = waves * ks * ntw * 2.0;               // two transposing reads per B fragment
+    m.lds_cycles = a_reads * kReadB128 + b_reads * kReadTr + (2.0 * T_MC * T_K + 2.0 * T_K * T_N) / kWriteBytesPerClk;
+    m.vmem_cycles = (1.125 * T_MC * T_K + 2.0 * T_K * T_N) / kVmemBytesPerClk;
+    m.steady_cycles = std::max(std::max(m.mfma_cycles, m.valu_cycles), std::max(m.lds_cycles, m.vmem_cycles)) / kCoIssue;
+    const double waves_per_simd = waves * wg_per_cu / 4.0;
+    m.switch_cycles = (kLdsLatency + waves * ks * kReadB128 + kBarrier) / std::max(1.0, waves_per_simd);
+    m.kstep_cycles = m.steady_cycles + rho * m.switch_cycles;
+    m.mfma_util = m.mfma_cycles / m.kstep_cycles;
+    m.clock_hz = std::min(2.4e9, 1.248e9 * std::pow(m.mfma_util, -0.6));
+    m.pred_flops = m.n_mfma * 32768.0 * 256.0 / (m.kstep_cycles / m.clock_hz);
+    *out = m;
+    return ATB_OK;
+}
+
+extern "C" atb_status atb_instance_geometry(int index, int *wave_m, int *wave_n, int *wg_per_cu)
+{
+    if (index < 0 || index >= atb::instance_count()) return ATB_ERR_INVALID_ARG;
+    const atb::Instance &x = atb::instance(index);
+    if (wave_m) *wave_m = x.wave_m;
+    if (wave_n) *wave_n = x.wave_n;
+    if (wg_per_cu) *wg_per_cu = x.wg_per_cu;
+    return ATB_OK;
+}

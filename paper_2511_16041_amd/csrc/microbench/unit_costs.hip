@@ -1,0 +1,121 @@
+// Unit costs of the gfx950 CU that the CDNA4 microkernel model (atb_model_microkernel) is built
+// from: how long an 8-pass MFMA holds the matrix pipe and the SIMD's VALU issue port, what another
+// VALU instruction costs next to it, and what the LDS charges for the three access kinds of the
+// GEMM kernel.  Developer tool, not part of libatb: build with
+//     hipcc --offload-arch=gfx950 -O3 -std=c++17 -Xclang -target-feature -Xclang -packed-fp32-ops -o unit_costs unit_costs.hip
+// and run on the GPU; it prints one line per experiment.  Every kernel runs one 512-thread workgroup
+// per CU (two waves per SIMD, as the GEMM does), a fixed number of iterations, and touches only its own
+// LDS and one output word per thread.  It prints nanoseconds; run it under
+//     rocprofv3 --pmc GRBM_GUI_ACTIVE --output-format csv -d <dir> -o p -- ./unit_costs
+// as well: GRBM_GUI_ACTIVE / 8 of a dispatch is its length in shader clocks (the clock depends on the
+// load, so each experiment has its own), which turns the figures into cycles.
+#include <hip/hip_runtime.h>
+#include <cstdio>
+#include <cstdlib>
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef int intx4 __attribute__((ext_vector_type(4)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
+
+#define CK(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) { printf("HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__); exit(1); } } while (0)
+#define FENCE() __builtin_amdgcn_sched_barrier(0)
+
+constexpr int kThreads = 512, kBlocks = 256, kLds = 64 * 1024;
+
+__device__ __forceinline__ float byte_to_float(int w, int b) { return (float)(int)(signed char)(w >> (8 * b)); }
+
+// MODE 0: 8 MFMAs per iteration, each followed by PAIRS BFP16 decode pairs (2 cvt, 2 ldexp, 1 pack).
+// MODE 1: 8 b128 fragment reads per iteration (lane l: row l % 32 at pitch 144, k half l / 32).
+// MODE 2: 8 transposing b64 reads per iteration (the swizzled B-tile pattern of the GEMM).
+// MODE 3: 8 b128 writes per iteration (the A staging pattern: 4 lanes per row of pitch 144).
+template <int MODE, int PAIRS>
+__global__ void __launch_bounds__(kThreads) cost_kernel(float *out, int iters, int seed)
+{
+    __shared__ __attribute__((aligned(16))) char lds[kLds];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    for (int i = t; i < kLds / 4; i += kThreads) reinterpret_cast<int *>(lds)[i] = i * seed;
+    __syncthreads();
+    bf16x8 a, b;
+    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)(float)((t + e) % 3); b[e] = (__bf16)(float)((t + e) % 5); }
+    floatx16 acc[8];
+    for (int i = 0; i < 8; ++i) for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    int w0 = seed + t, sh = seed & 3;
+    unsigned dsum = 0;
+    intx4 rsum = {0, 0, 0, 0};
+    const char *frag = lds + (wave & 3) * 4608 + (lane & 31) * 144 + (lane >> 5) * 16;           // < 18.5 KiB + 4.7 KiB
+    const char *frag_alt = lds + ((wave + 1) & 3) * 4608 + (lane & 31) * 144 + (lane >> 5) * 16;
+    const int blk = lane >> 4, j = lane & 15, r = j >> 2;
+    const char *tr = lds + 24576 + (8 * (blk >> 1) + r) * 512 + (((4 * (wave & 3) + 2 * (blk & 1) + ((j & 3) >> 1)) ^ (r << 2)) * 16) + (j & 1) * 8;   // 16 rows x 512 B
+    char *wr = lds + 36864 + (t >> 2) * 144 + (t & 3) * 32;                                        // 128 rows x 144 B
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (MODE == 0) {
+                acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+                FENCE();
+#pragma unroll
+                for (int v = 0; v < PAIRS; ++v) {
+                    const float f0 = ldexpf(byte_to_float(w0, (2 * v) & 3), sh), f1 = ldexpf(byte_to_float(w0, (2 * v + 1) & 3), sh);
+                    union { bf16x2 p; unsigned u; } pk;
+                    pk.p = bf16x2{(__bf16)f0, (__bf16)f1};
+                    dsum ^= pk.u;
+                    w0 += 0x01010101;
+                }
+                FENCE();
+            } else if (MODE == 1) {
+                rsum += *reinterpret_cast<const intx4 *>(((i >> 2) ? frag_alt : frag) + (i & 3) * 32);
+                asm volatile("" ::: "memory");
+            } else if (MODE == 2) {
+                typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
+                const shortx4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(tr + (i & 1) * 2048 + ((i >> 1) & 1) * 256));
+                rsum.x += v[0]; rsum.y += v[3];
+                asm volatile("" ::: "memory");
+            } else {
+                *reinterpret_cast<intx4 *>(wr + (i & 1) * 16) = intx4{w0, it, i, sh};
+                asm volatile("" ::: "memory");
+            }
+        }
+    }
+    float s = (float)(rsum.x + rsum.y + rsum.z + rsum.w) + (float)dsum;
+    for (int i = 0; i < 8; ++i) for (int q = 0; q < 16; ++q) s += acc[i][q];
+    __syncthreads();
+    s += reinterpret_cast<const float *>(lds)[t];
+    out[blockIdx.x * kThreads + t] = s;
+}
+
+template <int MODE, int PAIRS>
+double run(float *out, int iters)     // nanoseconds per iteration
+{
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
+    hipLaunchKernelGGL((cost_kernel<MODE, PAIRS>), dim3(kBlocks), dim3(kThreads), 0, 0, out, 200, 1);
+    CK(hipDeviceSynchronize());
+    CK(hipEventRecord(e0));
+    hipLaunchKernelGGL((cost_kernel<MODE, PAIRS>), dim3(kBlocks), dim3(kThreads), 0, 0, out, iters, 1);
+    CK(hipEventRecord(e1));
+    CK(hipEventSynchronize(e1));
+    float ms;
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    return ms * 1e6 / iters;
+}
+
+int main()
+{
+    float *out;
+    CK(hipMalloc(&out, kBlocks * kThreads * sizeof(float)));
+    const int iters = 20000;
+    printf("every experiment: %d workgroups x %d threads, %d iterations (after a 200-iteration warm-up launch of the same kernel)\n", kBlocks, kThreads, iters);
+    double c[4];
+    // an iteration issues 8 MFMAs per wave, 16 per SIMD (two waves)
+    c[0] = run<0, 0>(out, iters) / 16.0; printf("cost_kernel<0,0>  MFMA 32x32x16 bf16, 0 decode pairs per MFMA: %6.2f ns per MFMA per SIMD\n", c[0]);
+    c[1] = run<0, 1>(out, iters) / 16.0; printf("cost_kernel<0,1>  MFMA 32x32x16 bf16, 1 decode pair  per MFMA: %6.2f ns per MFMA per SIMD\n", c[1]);
+    c[2] = run<0, 2>(out, iters) / 16.0; printf("cost_kernel<0,2>  MFMA 32x32x16 bf16, 2 decode pairs per MFMA: %6.2f ns per MFMA per SIMD\n", c[2]);
+    c[3] = run<0, 3>(out, iters) / 16.0; printf("cost_kernel<0,3>  MFMA 32x32x16 bf16, 3 decode pairs per MFMA: %6.2f ns per MFMA per SIMD\n", c[3]);
+    // LDS: 8 waves x 8 instructions per iteration per CU
+    double x = run<1, 0>(out, iters) / 64.0; printf("cost_kernel<1,0>  ds_read_b128 (A fragment pattern):       %5.2f ns per wave instruction per CU, %6.1f B/ns\n", x, 1024.0 / x);
+    x = run<2, 0>(out, iters) / 64.0;        printf("cost_kernel<2,0>  ds_read_b64_tr_b16 (B fragment pattern): %5.2f ns per wave instruction per CU, %6.1f B/ns\n", x, 512.0 / x);
+    x = run<3, 0>(out, iters) / 64.0;        printf("cost_kernel<3,0>  ds_write_b128 (A staging pattern):       %5.2f ns per wave instruction per CU, %6.1f B/ns\n", x, 1024.0 / x);
+    return 0;
+}

@@ -178,3 +178,40 @@ def test_selector_tracks_problem_size():
     b = atb.select_tiles(1024, 1024, 1024)[0].pred_flops
     c = atb.select_tiles(8192, 8192, 8192)[0].pred_flops
     assert a < b < c and a < 2.0 * 256 ** 3 / 6e-6
+
+
+def test_microkernel_model_against_measurements():
+    """The CDNA4 issue model (unit costs measured by csrc/microbench/unit_costs.hip) against the
+    measured full-load throughput and MFMA-busy fraction of every compiled instance."""
+    import os
+    rows = []
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "mi355x_instances.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        f = line.split()
+        rows.append((tuple(int(x) for x in f[:4]), tuple(int(x) for x in f[4:7]), float(f[7]),
+                     None if f[8] == "-" else float(f[8]), f[9]))
+    inst = atb.instances()
+    assert {r[0] for r in rows} == set(inst)
+    for tiles, geom, tflops, busy, flag in rows:
+        assert atb.instance_geometry(inst.index(tiles)) == geom
+        m = atb.model_microkernel(*tiles, *geom)
+        # components as documented in include/atb.h
+        assert m.n_mfma == tiles[1] * tiles[3] * tiles[2] / 16384 and m.mfma_cycles == m.n_mfma * 8
+        assert m.steady_cycles == pytest.approx(max(m.mfma_cycles, m.valu_cycles, m.lds_cycles, m.vmem_cycles) / 0.85)
+        assert m.kstep_cycles == pytest.approx(m.steady_cycles + (tiles[1] // tiles[0]) * m.switch_cycles)
+        assert m.mfma_util == pytest.approx(m.mfma_cycles / m.kstep_cycles) and 0 < m.mfma_util < 1
+        if flag == "ok":
+            assert abs(m.pred_flops / 1e12 / tflops - 1) < 0.15, (tiles, m.pred_flops / 1e12, tflops)
+            if busy is not None:
+                assert abs(m.mfma_util - busy) < 0.10, (tiles, m.mfma_util, busy)
+    # every large tile is limited by the VALU issue port (decode next to MFMAs), the small ones by the LDS
+    big = atb.model_microkernel(128, 256, 64, 256, 2, 4, 1)
+    assert big.valu_cycles > big.mfma_cycles > big.lds_cycles * 0.9 and big.valu_cycles > big.lds_cycles
+    small = atb.model_microkernel(64, 64, 64, 64, 2, 2, 4)
+    assert small.lds_cycles > small.valu_cycles > small.mfma_cycles
+    L = atb.lib()
+    assert L.atb_model_microkernel(128, 256, 64, 256, 2, 4, 1, None) == 1
+    mm = atb.MicroModel()
+    assert L.atb_model_microkernel(96, 256, 64, 256, 2, 4, 1, ctypes.byref(mm)) == 2      # rho not an integer
+    assert L.atb_model_microkernel(128, 256, 64, 256, 3, 4, 1, ctypes.byref(mm)) == 2     # bands do not divide
