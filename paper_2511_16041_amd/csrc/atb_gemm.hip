@@ -125,7 +125,7 @@ constexpr int kOutOfRange = (int)0x80000000;     // a byte offset no buffer of o
 #define ATB_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 // Developer ablation switches (timing experiments only; results are wrong when non-zero):
-// 1 no decode arithmetic, 2 B fragments read once, 4 global loads once, 8 no LDS stores,
+// 2 B fragments read once, 4 global loads once, 8 no LDS stores,
 // 16 no A-fragment reads after the first band, 32 no MFMA, 64 no barrier,
 // 128 global loads never advance (always the first K-step: cache-hot), 256 no A loads, 512 no B loads.
 #ifndef ATB_ABLATE
@@ -194,6 +194,8 @@ struct TileKernel {
     static constexpr int BPT = BBFP ? 0 : (ROLE == 0) ? S::B_SLABS : (ROLE == 1) ? S::BO : S::B_SLABS - S::BO;   // bf16 B chunks per thread per tile
     static constexpr int BTPT = !BBFP ? 0 : (ROLE == 1) ? 0 : S::BT_SLABS;               // BFP16 B chunks (16 mantissas) per thread per tile
     static constexpr int NPAIR_B = BTPT * 8;                                             // B mantissa pairs per thread per tile
+    static constexpr int NSTEP_A = NPAIR > 0 ? NPAIR + 2 : 0;                            // decode pipeline steps per phase (A sub-tile)
+    static constexpr int NSTEP_B = NPAIR_B > 0 ? NPAIR_B / S::RHO + 2 : 0;               // ... and for this phase's share of the B tile
     static constexpr int APTN = APT > 0 ? APT : 1, BPTN = BPT > 0 ? BPT : 1, BTPTN = BTPT > 0 ? BTPT : 1;   // array extents
     static constexpr int B_BYTES = BBFP ? S::BT_BYTES : S::B_BYTES;
     static_assert(!BBFP || (NPAIR_B % S::RHO == 0 && S::T_K % 16 == 0 && (S::T_N * S::T_K / 16) % NTS == 0), "BFP16 B staging must split evenly");
@@ -236,6 +238,7 @@ struct TileKernel {
     unsigned a_expo[S::PF][APTN];
     intx4 b_raw[BPTN];
     unsigned dec[4];                   // bf16 pairs of the BFP16 block being decoded
+    float cvf[2][2], ldf[2][2];        // decode pipeline: converted and scaled pairs in flight
     int shift;
     ATB_TRACE_DECL;
 
@@ -479,29 +482,55 @@ struct TileKernel {
     }
 
     // ---- registers -> LDS ----------------------------------------------------------------
-    // Decode mantissa pair t of chunk i of register set `set` (exact: |m| <= 127 has 7 significant
-    // bits, bf16 keeps 8); after the 4th pair of a BFP16 block, write the block to LDS
-    // (bf16, [row][k], pitch PA).
-    template <int set, int i, int t>
-    ATB_DEV void decode_pair(char *a_dst)
+    // BFP16 decode of mantissa pairs (exact: |m| <= 127 has 7 significant bits, bf16 keeps 8), as a
+    // three-stage software pipeline over the pairs [first, first + count) of register set `set`:
+    // step u converts pair u to fp32 (two v_cvt_f32_i32 with a byte select), scales pair u-1 by its
+    // block's 2^(E-133) (two v_ldexp_f32) and packs pair u-2 to bf16 (one v_cvt_pk_bf16_f32); after
+    // the 4th pair of a BFP16 block the block goes to LDS (bf16, [row][k], pitch PA).  The five
+    // instructions of a step do not depend on each other: issued back to back as one dependent chain
+    // per pair they cost 6.5 cycles each next to MFMAs, independent ones 4.  count + 2 steps drain it.
+    // ISB selects the BFP16 B tile (chunks of 16 mantissas) instead of the A sub-tile.
+    template <bool ISB, int set, int first, int count, int u>
+    ATB_DEV void decode_step(char *dst_base)
     {
-        if constexpr (t % 4 == 0) shift = (int)((a_expo[set][i] >> (e_shift + 8 * (t / 4))) & 0xFFu) - 133;
-        const int w = a_mant[set][i][t / 2];
-        if constexpr (ATB_ABLATE & 1) {
-            dec[t % 4] = (unsigned)w + (unsigned)shift;
-        } else {
-            const float f0 = ldexpf(mant_to_float(w, (t % 2) * 2), shift);
-            const float f1 = ldexpf(mant_to_float(w, (t % 2) * 2 + 1), shift);
-            union { bf16x2 v; unsigned u; } pk;
-            pk.v = bf16x2{(__bf16)f0, (__bf16)f1};
-            dec[t % 4] = pk.u;
+        constexpr int PPC = ISB ? 8 : ACE / 2;                       // pairs per chunk
+        constexpr int ROWS = ISB ? NTS / (S::T_K / 16) : NTS / A_CPR; // LDS rows between a thread's chunks
+        if constexpr (u >= 2 && u - 2 < count) {
+            constexpr int j = first + u - 2, i = j / PPC, t = j % PPC;
+            union { bf16x2 v; unsigned w; } pk;
+            pk.v = bf16x2{(__bf16)ldf[(u - 2) % 2][0], (__bf16)ldf[(u - 2) % 2][1]};
+            dec[t % 4] = pk.w;
+            if constexpr (t % 4 == 3) {
+                char *dst = dst_base + i * ROWS * S::PA + (t / 4) * 16;
+                if constexpr (ATB_ABLATE & 8)
+                    asm volatile("" ::"v"(dec[0]), "v"(dec[1]), "v"(dec[2]), "v"(dec[3]));
+                else
+                    *reinterpret_cast<intx4 *>(dst) = intx4{(int)dec[0], (int)dec[1], (int)dec[2], (int)dec[3]};
+            }
         }
-        if constexpr (t % 4 == 3) {
-            char *dst = a_dst + i * (NTS / A_CPR) * S::PA + (t / 4) * 16;
-            if constexpr (ATB_ABLATE & 8)
-                asm volatile("" ::"v"(dec[0]), "v"(dec[1]), "v"(dec[2]), "v"(dec[3]));
-            else
-                *reinterpret_cast<intx4 *>(dst) = intx4{(int)dec[0], (int)dec[1], (int)dec[2], (int)dec[3]};
+        if constexpr (u >= 1 && u - 1 < count) {
+            constexpr int j = first + u - 1, i = j / PPC, t = j % PPC;
+            if constexpr (t % 4 == 0 || u == 1) {
+                const unsigned e = ISB ? bt_expo[set][i] : a_expo[set][i];
+                shift = (int)((e >> ((ISB ? eb_shift : e_shift) + 8 * (t / 4))) & 0xFFu) - 133;
+            }
+            ldf[(u - 1) % 2][0] = ldexpf(cvf[(u - 1) % 2][0], shift);
+            ldf[(u - 1) % 2][1] = ldexpf(cvf[(u - 1) % 2][1], shift);
+        }
+        if constexpr (u < count) {
+            constexpr int j = first + u, i = j / PPC, t = j % PPC;
+            const int w = ISB ? bt_mant[set][i][t / 2] : a_mant[set][i][t / 2];
+            cvf[u % 2][0] = mant_to_float(w, (t % 2) * 2);
+            cvf[u % 2][1] = mant_to_float(w, (t % 2) * 2 + 1);
+        }
+    }
+
+    template <bool ISB, int set, int first, int count, int u = 0>
+    ATB_DEV void decode_all(char *dst_base)
+    {
+        if constexpr (count > 0 && u < count + 2) {
+            decode_step<ISB, set, first, count, u>(dst_base);
+            decode_all<ISB, set, first, count, u + 1>(dst_base);
         }
     }
 
@@ -514,40 +543,11 @@ struct TileKernel {
             *reinterpret_cast<intx4 *>(b_dst + i * (NTS * 16)) = b_raw[i];
     }
 
-    template <int set, int j = 0>
-    ATB_DEV void store_a_all(char *a_dst)
-    {
-        if constexpr (j < NPAIR) {
-            decode_pair<set, j / (ACE / 2), j % (ACE / 2)>(a_dst);
-            store_a_all<set, j + 1>(a_dst);
-        }
-    }
+    template <int set>
+    ATB_DEV void store_a_all(char *a_dst) { decode_all<false, set, 0, NPAIR>(a_dst); }
 
-    // Same for pair t (0..7) of chunk i of the BFP16 B tile in register set `set`.
-    template <int set, int i, int t>
-    ATB_DEV void decode_bt_pair(char *b_dst)
-    {
-        if constexpr (t % 4 == 0) shift = (int)((bt_expo[set][i] >> (eb_shift + 8 * (t / 4))) & 0xFFu) - 133;
-        const int w = bt_mant[set][i][t / 2];
-        const float f0 = ldexpf(mant_to_float(w, (t % 2) * 2), shift);
-        const float f1 = ldexpf(mant_to_float(w, (t % 2) * 2 + 1), shift);
-        union { bf16x2 v; unsigned u; } pk;
-        pk.v = bf16x2{(__bf16)f0, (__bf16)f1};
-        dec[t % 4] = pk.u;
-        if constexpr (t % 4 == 3) {
-            char *dst = b_dst + i * (NTS / (S::T_K / 16)) * S::PA + (t / 4) * 16;
-            *reinterpret_cast<intx4 *>(dst) = intx4{(int)dec[0], (int)dec[1], (int)dec[2], (int)dec[3]};
-        }
-    }
-
-    template <int set, int j = 0>
-    ATB_DEV void store_bt_all(char *b_dst)
-    {
-        if constexpr (j < NPAIR_B) {
-            decode_bt_pair<set, j / 8, j % 8>(b_dst);
-            store_bt_all<set, j + 1>(b_dst);
-        }
-    }
+    template <int set>
+    ATB_DEV void store_bt_all(char *b_dst) { decode_all<true, set, 0, NPAIR_B>(b_dst); }
 
     template <int i = 0>
     ATB_DEV void store_b_all(char *b_dst)
@@ -611,7 +611,7 @@ struct TileKernel {
     template <int s>
     static constexpr int n_side()
     {
-        return APT + (s == 0 ? BPT + BTPT : 0) + NPAIR + NPAIR_B / S::RHO + ((!VEC && s + 1 == S::RHO) ? BPT : 0);
+        return APT + (s == 0 ? BPT + BTPT : 0) + NSTEP_A + NSTEP_B + ((!VEC && s + 1 == S::RHO) ? BPT : 0);
     }
 
     template <int ki, int s, int j>
@@ -620,7 +620,7 @@ struct TileKernel {
         constexpr int kpar = ki & 1;             // parity of the K-step: B buffers and B register sets
         constexpr int g = ki * S::RHO + s;       // running sub-tile index within the loop body
         constexpr int n_la = APT, n_lb = (s == 0 ? BPT : 0), n_lt = (s == 0 ? BTPT : 0), n_dt = NPAIR_B / S::RHO;
-        constexpr int j1 = n_lb, j2 = j1 + n_lt, j3 = j2 + n_la, j4 = j3 + NPAIR, j5 = j4 + n_dt;
+        constexpr int j1 = n_lb, j2 = j1 + n_lt, j3 = j2 + n_la, j4 = j3 + NSTEP_A, j5 = j4 + NSTEP_B;
         if constexpr (j < j1) {
             if constexpr (!(ATB_ABLATE & 512)) load_b_chunk<j>(kpar);
         } else if constexpr (j < j2) {
@@ -628,10 +628,9 @@ struct TileKernel {
         } else if constexpr (j < j3) {
             if constexpr (!(ATB_ABLATE & 256)) load_a_chunk<g % S::PF, (s + S::PF) % S::RHO, j - j2>();
         } else if constexpr (j < j4) {
-            decode_pair<(g + S::DA) % S::PF, (j - j3) / (ACE / 2), (j - j3) % (ACE / 2)>(a_wr[(g + S::DA) % S::AB]);
+            decode_step<false, (g + S::DA) % S::PF, 0, NPAIR, j - j3>(a_wr[(g + S::DA) % S::AB]);
         } else if constexpr (j < j5) {
-            constexpr int q = s * n_dt + (j - j4);
-            decode_bt_pair<kpar, q / 8, q % 8>(bt_wr[kpar]);
+            decode_step<true, kpar, s * n_dt, n_dt, j - j4>(bt_wr[kpar]);
         } else {
             store_b_chunk<j - j5>(b_wr[kpar]);
         }
