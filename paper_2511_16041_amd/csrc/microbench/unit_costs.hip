@@ -30,6 +30,8 @@ __device__ __forceinline__ float byte_to_float(int w, int b) { return (float)(in
 // MODE 1: 8 b128 fragment reads per iteration (lane l: row l % 32 at pitch 144, k half l / 32).
 // MODE 2: 8 transposing b64 reads per iteration (the swizzled B-tile pattern of the GEMM).
 // MODE 3: 8 b128 writes per iteration (the A staging pattern: 4 lanes per row of pitch 144).
+// MODE 4: MODE 0 with pseudo-random bf16 operands (random sign and mantissa, exponents 2^-7 .. 2): the
+//         matrix pipes draw more power than on constants, and the chip answers with a lower clock.
 template <int MODE, int PAIRS>
 __global__ void __launch_bounds__(kThreads) cost_kernel(float *out, int iters, int seed)
 {
@@ -39,6 +41,15 @@ __global__ void __launch_bounds__(kThreads) cost_kernel(float *out, int iters, i
     __syncthreads();
     bf16x8 a, b;
     for (int e = 0; e < 8; ++e) { a[e] = (__bf16)(float)((t + e) % 3); b[e] = (__bf16)(float)((t + e) % 5); }
+    if (MODE == 4) {
+        union { unsigned u[4]; bf16x8 v; } ua, ub;
+        unsigned r = t * 2654435761u + 12345u;
+        for (int e = 0; e < 4; ++e) {
+            r = r * 1664525u + 1013904223u; ua.u[e] = (r & 0x807F807Fu) | 0x3C003C00u | ((r >> 3) & 0x03800380u);
+            r = r * 1664525u + 1013904223u; ub.u[e] = (r & 0x807F807Fu) | 0x3C003C00u | ((r >> 3) & 0x03800380u);
+        }
+        a = ua.v; b = ub.v;
+    }
     floatx16 acc[8];
     for (int i = 0; i < 8; ++i) for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
     int w0 = seed + t, sh = seed & 3;
@@ -52,7 +63,7 @@ __global__ void __launch_bounds__(kThreads) cost_kernel(float *out, int iters, i
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            if (MODE == 0) {
+            if (MODE == 0 || MODE == 4) {
                 acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
                 FENCE();
 #pragma unroll
@@ -117,5 +128,9 @@ int main()
     double x = run<1, 0>(out, iters) / 64.0; printf("cost_kernel<1,0>  ds_read_b128 (A fragment pattern):       %5.2f ns per wave instruction per CU, %6.1f B/ns\n", x, 1024.0 / x);
     x = run<2, 0>(out, iters) / 64.0;        printf("cost_kernel<2,0>  ds_read_b64_tr_b16 (B fragment pattern): %5.2f ns per wave instruction per CU, %6.1f B/ns\n", x, 512.0 / x);
     x = run<3, 0>(out, iters) / 64.0;        printf("cost_kernel<3,0>  ds_write_b128 (A staging pattern):       %5.2f ns per wave instruction per CU, %6.1f B/ns\n", x, 1024.0 / x);
+    // power: long runs (0.1 - 0.2 s, the chip's power management needs that long to settle), constants vs random operands
+    x = run<0, 0>(out, 1000000) / 16.0; printf("cost_kernel<0,0>  MFMA only, constant operands, 1e6 iterations: %6.2f ns per MFMA per SIMD = %.0f TFLOP/s\n", x, 32768.0 * 1024 / x / 1e3);
+    x = run<4, 0>(out, 1000000) / 16.0; printf("cost_kernel<4,0>  MFMA only, random operands,   1e6 iterations: %6.2f ns per MFMA per SIMD = %.0f TFLOP/s\n", x, 32768.0 * 1024 / x / 1e3);
+    x = run<4, 1>(out, 1000000) / 16.0; printf("cost_kernel<4,1>  random operands + 1 decode pair per MFMA:     %6.2f ns per MFMA per SIMD = %.0f TFLOP/s\n", x, 32768.0 * 1024 / x / 1e3);
     return 0;
 }
