@@ -155,3 +155,16 @@ def test_run_rejects_bad_arguments():
     assert L.atb_gemm_run(g._h, None, p, p, None) == 1
     assert L.atb_gemm_run(g._h, ctypes.c_void_p(buf.data_ptr() + 2), p, p, None) == 1      # misaligned
     g.close()
+
+
+@pytest.mark.parametrize("tiles", BIG + WIDE_K)
+def test_more_tiles_than_resident_workgroups(tiles):
+    """17 x 18 = 306 tiles of 256 x 256 on 256 CUs: the persistent grid gives some workgroups a second
+    tile (registers, LDS buffers and in-flight requests of the first must not leak into it), and the
+    per-XCD runs of tiles are not a multiple of anything."""
+    M, N, K = 4300, 4400, 136
+    print(f"gemm persistent {tiles}", flush=True)
+    A, Bb = workloads.make_inputs(workloads.CONFIGS["ragged"], M=M, N=N, K=K)
+    mant, expo = oracle.quantize(A)
+    C_ref, T, _ = oracle.gemm(mant, expo, Bb)
+    _check(_run(mant, expo, Bb, tiles), C_ref, T, f"persistent {tiles}")
