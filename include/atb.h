@@ -106,9 +106,9 @@ typedef enum atb_format {
  *                   (blocks of 8 along N), quantised from the fp32
  *                   accumulators by the same rule as atb_bfp16_quantize;
  *                   rows are fully written including their zero padding.
- * Formats other than (BF16, BF16) need N % 8 == 0 and one of the instances
- * with T_MC = T_N = 256, T_K = 64, T_MA in {256, 128, 64}; otherwise
- * ATB_ERR_INVALID_ARG / ATB_ERR_BAD_TILE.  All else as atb_gemm_create. */
+ * Formats other than (BF16, BF16) need N % 8 == 0 (else ATB_ERR_INVALID_ARG)
+ * and an instance that carries the variants: all but (32, 256, 64, 256) and
+ * (32, 256, 128, 256) (else ATB_ERR_BAD_TILE).  All else as atb_gemm_create. */
 atb_status atb_gemm_create_fmt(atb_gemm **out, int64_t M, int64_t N, int64_t K,
                                int T_MA, int T_MC, int T_K, int T_N,
                                atb_format b_format, atb_format c_format);

@@ -1,4 +1,5 @@
 // C ABI of libatb (see include/atb.h): argument checking, plans, launches.
+#include <algorithm>
 #include <cstdlib>
 #include <new>
 
@@ -151,7 +152,10 @@ extern "C" atb_status atb_gemm_create_fmt(atb_gemm **out, int64_t M, int64_t N, 
     p.lde = (int)g->layout.lde;
     p.tiles_m = (int)((M + T_MC - 1) / T_MC);
     p.tiles_n = (int)((N + T_N - 1) / T_N);
-    p.group_m = 8;
+    // C in BFP16: the tiles also cover the zero padding of the C rows (N .. ldcm - 1), so that the
+    // result can be the BFP16 operand of a following GEMM as it is
+    if (c_format == ATB_FMT_BFP16) p.tiles_n = (int)((atb::round_up(N, 128) + T_N - 1) / T_N);
+    p.group_m = (int)std::max<int64_t>(1, 2048 / T_MC);   // an XCD's patch of C tiles is 2048 rows high
     *out = g;
     return ATB_OK;
 }

@@ -960,7 +960,8 @@ const Instance g_instances[] = {
     // requests all of B, except at rho = 1, where a quarter of the (large) A tile goes to the second
     // group as well (measured on 8192^3: 1195 against 1164 TFLOP/s for the even split and 950 for 4 : 0).
     // The A fetch runs one to one and a half K-steps ahead of its use at every rho (PF phases).
-    // These three also come with B and/or C stored as BFP16 (the all-BFP16 configurations of Sec. 6.1).
+    // These three, and the mid-size and small tiles below, also come with B and/or C stored as BFP16
+    // (the all-BFP16 configurations of Sec. 6.1); the 4-wave 256-row instances have no registers left for it.
     make_instance<Shape<256, 256, 64, 256, 2, 4, 2, 2, 3, 0>, true>(),
     make_instance<Shape<128, 256, 64, 256, 2, 4, 2, 2, 2, 0>, true>(),
     make_instance<Shape<64, 256, 64, 256, 2, 4, 4, 2, 1, 0>, true>(),
@@ -973,13 +974,13 @@ const Instance g_instances[] = {
     // (the factors are measured full-load throughput over the 256 x 256 family's fit: workgroups that
     // share a CU overlap each other's barriers and latencies, which the per-tile formula does not see;
     // the symmetric 128 x 256 tile has a single barrier per short K-step and waits for its B tile there)
-    make_instance<Shape<128, 128, 64, 256, 2, 4, 2, 2>>(0.50),
-    make_instance<Shape<64, 128, 64, 256, 2, 4, 4, 2>>(0.92),
-    make_instance<Shape<128, 128, 64, 128, 2, 2, 2, 2>>(1.07),
-    make_instance<Shape<64, 128, 64, 128, 2, 2, 4, 2>>(1.16),
+    make_instance<Shape<128, 128, 64, 256, 2, 4, 2, 2>, true>(0.50),
+    make_instance<Shape<64, 128, 64, 256, 2, 4, 4, 2>, true>(0.92),
+    make_instance<Shape<128, 128, 64, 128, 2, 2, 2, 2>, true>(1.07),
+    make_instance<Shape<64, 128, 64, 128, 2, 2, 4, 2>, true>(1.16),
     // small tiles for small problems
-    make_instance<Shape<64, 64, 64, 64, 2, 2, 2, 2>>(1.47),
-    make_instance<Shape<32, 64, 64, 64, 1, 2, 2, 2>>(1.33),
+    make_instance<Shape<64, 64, 64, 64, 2, 2, 2, 2>, true>(1.47),
+    make_instance<Shape<32, 64, 64, 64, 1, 2, 2, 2>, true>(1.33),
 };
 
 

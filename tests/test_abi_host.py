@@ -164,7 +164,9 @@ def test_create_fmt_validation():
     assert create(512, 508, 256, (128, 256, 64, 256), 1, 0) == 1 and not h.value  # N % 8 != 0
     assert create(512, 512, 256, (128, 256, 64, 256), 2, 0) == 1                  # unknown format
     assert create(512, 512, 256, (32, 256, 64, 256), 0, 1) == 2                   # instance without format variants
-    assert create(512, 512, 256, (64, 64, 64, 64), 1, 1) == 2
+    assert create(512, 512, 256, (32, 256, 128, 256), 1, 1) == 2
+    assert create(512, 512, 256, (64, 64, 64, 64), 1, 1) == 0 and h.value
+    L.atb_gemm_destroy(h)
 
 
 def test_selector_tracks_problem_size():

@@ -16,7 +16,8 @@ from helpers import bf16_tensor_bits, bits_to_bf16_tensor, pack_a_bfp, unpack_a_
 
 pytestmark = pytest.mark.gpu
 
-FMT_TILES = [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256)]
+FMT_TILES = [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256),
+             (128, 128, 64, 256), (64, 128, 64, 256), (128, 128, 64, 128), (64, 128, 64, 128), (64, 64, 64, 64), (32, 64, 64, 64)]
 COMBOS = [("bfp16", "bf16"), ("bf16", "bfp16"), ("bfp16", "bfp16")]
 
 
@@ -120,3 +121,32 @@ def test_format_argument_errors():
     with pytest.raises(atb.AtbError) as e:
         atb.Gemm(256, 256, 64, 32, 256, 64, 256, c_format="bfp16")
     assert e.value.status == 2
+
+
+@pytest.mark.parametrize("tiles", [(128, 256, 64, 256), (64, 64, 64, 64)])
+def test_bfp16_output_feeds_the_next_gemm(tiles):
+    """Two layers: C1 = A x B1 written as BFP16, then C2 = C1 x B2 with C1 taken as it is (its row
+    padding included) as the BFP16 operand.  Small-integer inputs make the first stage's sums exact, so the
+    oracle's own C1 codes equal the GPU's (asserted); stage 2 then has identical inputs on both sides and must
+    meet the GEMM tolerance."""
+    import torch
+    M, N1, K1, N2 = 300, 264, 200, 136
+    print(f"formats chain tiles={tiles}", flush=True)
+    A, B1 = workloads.small_integer_inputs(M, N1, K1, seed=11)
+    _, B2 = workloads.small_integer_inputs(8, N2, N1, seed=12)             # bf16 bits [N1][N2]
+    mant, expo = oracle.quantize(A)
+    _, _, S1, _ = oracle.gemm(mant, expo, B1, want_sum=True)
+    c1m, c1e = oracle.quantize(S1.astype(np.float32))
+    C2_ref, T2, _ = oracle.gemm(c1m, c1e, B2)
+
+    A_dev = torch.from_numpy(pack_a_bfp(mant, expo, atb.bfp16_layout(M, K1))).cuda()
+    g1 = atb.Gemm(M, N1, K1, *tiles, c_format="bfp16")
+    C1_dev = g1.run(A_dev, bits_to_bf16_tensor(B1, "cuda"), torch.full((atb.bfp16_bytes(M, N1),), 0xAB, dtype=torch.uint8, device="cuda"))
+    g2 = atb.Gemm(M, N2, N1, *tiles)
+    C2_dev = g2.run(C1_dev, bits_to_bf16_tensor(B2, "cuda"))
+    torch.cuda.synchronize()
+    g1.close(); g2.close()
+    gm, ge, pad = unpack_a_bfp(C1_dev.cpu().numpy(), M, N1, atb.bfp16_layout(M, N1))
+    assert np.array_equal(gm, c1m) and np.array_equal(ge, c1e) and not pad.any()
+    err = np.abs(oracle.bf16_to_double(bf16_tensor_bits(C2_dev)) - oracle.bf16_to_double(C2_ref))
+    assert not np.isnan(err).any() and not (err > oracle.tolerance(T2)).any()
