@@ -164,7 +164,7 @@ __device__ unsigned long long atb_trace_acc[16 * 8];
 //   A sub-tile g   : fetched from memory in phase g-PF into register set g % PF, decoded into LDS
 //                    buffer g % 2 during phase g-1, consumed by the microkernel of phase g.
 //   B tile kt      : requested in the first phase of K-step kt-2 straight into LDS buffer kt % 2
-//                    (N % 8 != 0: into registers, written to LDS in the last phase of K-step kt-2),
+//                    (odd N: into registers, written to LDS in the last phase of K-step kt-2),
 //                    awaited before the last barrier that precedes the last band of K-step kt-1,
 //                    read into the waves' fragment registers during that band (each fragment
 //                    right after its last use), consumed in K-step kt.
@@ -425,7 +425,7 @@ struct TileKernel {
     }
 
     // Request i of the next B tile in fetch order, destined for LDS buffer `buf`.
-    // VEC (N % 8 == 0): one 16-byte load per lane straight into LDS (no registers, no ds_write);
+    // VEC (even N: dword-aligned rows): one 16-byte load per lane straight into LDS (no registers, no ds_write);
     // completion is awaited with wait_b_landed() before the barrier that publishes the tile.
     // !VEC: element loads into registers, each masked against N; store_b_chunk() writes them later.
     template <int i>
@@ -918,7 +918,10 @@ hipError_t launch_kernel(const GemmParams &p, hipStream_t stream)
 template <class S>
 hipError_t launch_instance(const GemmParams &p, hipStream_t stream)
 {
-    if ((p.N % 8) == 0) return launch_kernel<S, true, false, false>(p, stream);
+    // 16-byte requests need dword-aligned addresses: B rows start at multiples of 2 N bytes, chunks at
+    // multiples of 16 bytes within a row, so any even N qualifies (a chunk that straddles the end of
+    // a row only feeds output columns >= N, which are never stored)
+    if ((p.N % 2) == 0) return launch_kernel<S, true, false, false>(p, stream);
     return launch_kernel<S, false, false, false>(p, stream);
 }
 

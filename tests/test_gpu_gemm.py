@@ -57,9 +57,10 @@ def test_small256_config(tiles):
 
 
 @pytest.mark.parametrize("tiles", SMALL + MID + BIG + WIDE_K)
-@pytest.mark.parametrize("shape", [(300, 500, 264), (257, 263, 72), (33, 20, 8), (1, 1, 8), (520, 516, 136), (300, 499, 64)])
+@pytest.mark.parametrize("shape", [(300, 500, 264), (257, 263, 72), (33, 20, 8), (1, 1, 8), (520, 516, 136), (300, 499, 64), (300, 502, 72), (130, 18, 24)])
 def test_ragged_shapes(tiles, shape):
-    """Several tiles plus ragged M and N tails, a K tail of 8, N not a multiple of 8 or of 4."""
+    """Several tiles plus ragged M and N tails, a K tail of 8, N not a multiple of 8, of 4 (rows of B only
+    dword-aligned) or of 2 (the element-load variant of the kernel)."""
     M, N, K = shape
     print(f"gemm ragged {shape} tiles={tiles}", flush=True)
     A, Bb = workloads.make_inputs(workloads.CONFIGS["ragged"], M=M, N=N, K=K)
