@@ -106,8 +106,8 @@ typedef enum atb_format {
  *                   (blocks of 8 along N), quantised from the fp32
  *                   accumulators by the same rule as atb_bfp16_quantize;
  *                   rows are fully written including their zero padding.
- * Formats other than (BF16, BF16) need N % 8 == 0 (else ATB_ERR_INVALID_ARG)
- * and an instance that carries the variants: all but (32, 256, 64, 256) and
+ * c_format BFP16 needs N % 8 == 0 (whole blocks; else ATB_ERR_INVALID_ARG);
+ * formats other than (BF16, BF16) need an instance that carries the variants: all but (32, 256, 64, 256) and
  * (32, 256, 128, 256) (else ATB_ERR_BAD_TILE).  All else as atb_gemm_create. */
 atb_status atb_gemm_create_fmt(atb_gemm **out, int64_t M, int64_t N, int64_t K,
                                int T_MA, int T_MC, int T_K, int T_N,

@@ -115,7 +115,7 @@ extern "C" atb_status atb_gemm_create_fmt(atb_gemm **out, int64_t M, int64_t N, 
     if ((b_format != ATB_FMT_BF16 && b_format != ATB_FMT_BFP16) || (c_format != ATB_FMT_BF16 && c_format != ATB_FMT_BFP16))
         return ATB_ERR_INVALID_ARG;
     const bool other_fmt = (b_format != ATB_FMT_BF16 || c_format != ATB_FMT_BF16);
-    if (other_fmt && (N % 8) != 0) return ATB_ERR_INVALID_ARG;
+    if (c_format == ATB_FMT_BFP16 && (N % 8) != 0) return ATB_ERR_INVALID_ARG;   // whole blocks along N
     if (N * atb::round_up(K, 128) >= ((int64_t)1 << 31) || M * atb::round_up(N, 128) >= ((int64_t)1 << 31))
         return ATB_ERR_INVALID_ARG;
     // 32-bit element offsets inside the kernel: keep every plane below 2^31 elements

@@ -925,7 +925,7 @@ hipError_t launch_instance(const GemmParams &p, hipStream_t stream)
     return launch_kernel<S, false, false, false>(p, stream);
 }
 
-// The other storage formats (B and/or C in BFP16); they need N % 8 == 0 (checked by the caller).
+// The other storage formats (B and/or C in BFP16); C in BFP16 needs N % 8 == 0 (checked by the caller).
 template <class S>
 hipError_t launch_instance_fmt(const GemmParams &p, int b_format, int c_format, hipStream_t stream)
 {

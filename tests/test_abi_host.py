@@ -161,7 +161,9 @@ def test_create_fmt_validation():
     L.atb_gemm_destroy(h)
     assert create(512, 512, 256, (128, 256, 64, 256), 0, 0) == 0 and h.value      # same as atb_gemm_create
     L.atb_gemm_destroy(h)
-    assert create(512, 508, 256, (128, 256, 64, 256), 1, 0) == 1 and not h.value  # N % 8 != 0
+    assert create(512, 508, 256, (128, 256, 64, 256), 0, 1) == 1 and not h.value  # C in BFP16: N % 8 != 0
+    assert create(512, 508, 256, (128, 256, 64, 256), 1, 0) == 0 and h.value      # B in BFP16 does not constrain N
+    L.atb_gemm_destroy(h)
     assert create(512, 512, 256, (128, 256, 64, 256), 2, 0) == 1                  # unknown format
     assert create(512, 512, 256, (32, 256, 64, 256), 0, 1) == 2                   # instance without format variants
     assert create(512, 512, 256, (32, 256, 128, 256), 1, 1) == 2

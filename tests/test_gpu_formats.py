@@ -112,10 +112,24 @@ def test_random_inputs(tiles, fmt, shape):
         assert not (err > tol).any(), f"worst ratio {np.max(err / tol):.3g}"
 
 
+@pytest.mark.parametrize("tiles", [(128, 256, 64, 256), (128, 128, 64, 128), (32, 64, 64, 64)])
+@pytest.mark.parametrize("shape", [(300, 263, 72), (129, 502, 136)])
+def test_bfp16_b_with_ragged_n(tiles, shape):
+    """B in BFP16 does not constrain N (its blocks run along K)."""
+    M, N, K = shape
+    print(f"formats ragged-N {shape} tiles={tiles}", flush=True)
+    A, Bt = _inputs(M, N, K, seed=5, exact=False)
+    mant, expo, bmant, bexpo, Bq_bits = _reference(A, Bt)
+    C_ref, T, _ = oracle.gemm(mant, expo, Bq_bits)
+    got = _run(mant, expo, (bmant, bexpo), M, N, K, tiles, "bfp16", "bf16")
+    err = np.abs(oracle.bf16_to_double(got) - oracle.bf16_to_double(C_ref))
+    assert not np.isnan(err).any() and not (err > oracle.tolerance(T)).any()
+
+
 def test_format_argument_errors():
-    # N not a multiple of 8
+    # C in BFP16 needs whole blocks along N
     with pytest.raises(atb.AtbError) as e:
-        atb.Gemm(256, 260, 64, 128, 256, 64, 256, b_format="bfp16")
+        atb.Gemm(256, 260, 64, 128, 256, 64, 256, c_format="bfp16")
     assert e.value.status == 1
     # an instance that has no BFP16 B / C variant
     with pytest.raises(atb.AtbError) as e:
