@@ -18,8 +18,12 @@
 //   * A sub-tiles are fetched from HBM/L2 as raw BFP16 (16 mantissa bytes +
 //     2 exponent bytes per lane), decoded to bf16 in registers (exact) and
 //     written to a double-buffered LDS area of only T_MA rows;
-//   * one workgroup barrier per sub-tile is the "kernel switch" of Sec. 5.
+//   * one workgroup barrier per sub-tile is the "kernel switch" of Sec. 5;
+//   * workgroups of 8 waves (two per SIMD) split the staging by kind: waves 0-3 stage A, waves 4-7
+//     stage B (see TileKernel); the grid of the 256 x 256 tiles is persistent (see tile_loop).
 // T_MA == T_MC is the symmetric baseline: same code, one sub-tile per K-step.
+// B may also arrive as BFP16 (as B^T, blocks along K) and C may be written as BFP16 (Sec. 6.1's
+// all-BFP16 storage); see the BBFP / CBFP template flags of TileKernel.
 //
 // MFMA: v_mfma_f32_32x32x16_bf16.  Operand lane layout: lane l supplies row
 // (l % 32) of its operand and the 8 consecutive k values 8*(l/32) .. +7, which
@@ -125,15 +129,16 @@ constexpr int kOutOfRange = (int)0x80000000;     // a byte offset no buffer of o
 #define ATB_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 // Developer ablation switches (timing experiments only; results are wrong when non-zero):
-// 2 B fragments read once, 4 global loads once, 8 no LDS stores,
-// 16 no A-fragment reads after the first band, 32 no MFMA, 64 no barrier,
-// 128 global loads never advance (always the first K-step: cache-hot), 256 no A loads, 512 no B loads.
+// 2 B fragments read once, 8 no LDS stores of decoded A, 16 no A-fragment reads after the first band,
+// 32 no MFMA, 64 no barrier, 128 global loads never advance (always the first K-step: cache-hot),
+// 256 no A loads, 512 no bf16 B loads, 1024 no exponent loads.
 #ifndef ATB_ABLATE
 #define ATB_ABLATE 0
 #endif
 
-// Cycle stamps for kernel tuning; compiled out of the library (ATB_TRACE is defined only by the
-// developer's own timing harness, which also supplies atb_trace_buf).
+// Per-wave time stamps for kernel tuning (s_memtime at the start of a microkernel, at its end and
+// after the switch barrier, summed per wave of workgroup 0); compiled out of the library: ATB_TRACE
+// is defined only by a developer's timing harness, which reads atb_trace_acc back.
 #ifdef ATB_TRACE
 __device__ unsigned long long atb_trace_acc[16 * 8];
 #define ATB_TRACE_DECL unsigned long long trace_prev = 0, trace_sum[8] = {}
