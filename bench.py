@@ -241,8 +241,8 @@ def main():
         lay = atb.bfp16_layout(M, K)
         raw = raw_a
         nrows = min(args.cpu_rows, M)
-        mant = raw[: M * lay.ldm].reshape(M, lay.ldm)[:nrows, :K].view(np.int8).copy()
-        expo = raw[lay.exp_off: lay.exp_off + M * lay.lde].reshape(M, lay.lde)[:nrows, : K // 8].copy()
+        mant, expo, _ = atb.bfp16_unpack_host(raw, M, K)
+        mant, expo = mant[:nrows].copy(), expo[:nrows].copy()
         t0 = time.perf_counter()
         _, _, threads = oracle.gemm(mant, expo, Bb)
         dt = time.perf_counter() - t0

@@ -24,15 +24,18 @@
  *     E uint8 = 127 + max over the block of floor(log2 |x|)  (0 for a zero block),
  *     m = clamp(round_to_nearest_even(x * 2^(133 - E)), -127, 127).
  *
- * Device layout of an A_bfp buffer (atb_bfp16_layout gives the numbers):
- *     mantissa plane  int8  [M][ldm]  at byte 0,        ldm = round_up(K, 128)
- *     exponent plane  uint8 [M][lde]  at byte exp_off,  lde = ldm / 8,
- *                                     exp_off = round_up(M * ldm, 256)
- *     total bytes = round_up(exp_off + M * lde, 256)
- *   Padding bytes of the mantissa plane (k >= K) MUST be zero; padding bytes
- *   of the exponent plane are ignored.  9 bytes per 8 elements as in the
- *   paper's packed bfp16ebs8 (plus row padding), but planar so that all loads are
- *   aligned and no K-step of the kernel ever leaves a row.
+ * Device layout of an A_bfp buffer for an M x K matrix (atb_bfp16_layout gives
+ * the numbers): K is cut into panels of 64; inside a panel the rows follow
+ * each other, so the part of a tile that one K-step needs is one contiguous
+ * run of bytes (the GEMM fetches it with fully coalesced 16-byte requests).
+ *     mantissa plane  int8  [panels][M][64]  at byte 0,
+ *                     panels = ceil(K / 64); m[i][k] at (k/64) * M*64 + i*64 + k%64
+ *     exponent plane  uint8 [panels][M][8]   at byte exp_off = round_up(panels * M * 64, 256);
+ *                     E[i][k/8] at exp_off + (k/64) * M*8 + i*8 + (k%64)/8
+ *     total bytes = round_up(exp_off + panels * M * 8, 256)
+ *   Mantissa bytes with k >= K (the tail of the last panel) MUST be zero; the
+ *   exponent bytes there are ignored.  9 bytes per 8 elements as in the
+ *   paper's packed bfp16ebs8, but planar so that all loads are aligned.
  * B: bf16, row-major K x N, leading dimension N.  C: bf16, row-major M x N,
  * leading dimension N.  A_bfp, B and C must be 16-byte aligned.
  */
@@ -105,7 +108,8 @@ typedef enum atb_format {
  *   c_format BFP16: C as a BFP16 buffer with the layout atb_bfp16_layout(M, N)
  *                   (blocks of 8 along N), quantised from the fp32
  *                   accumulators by the same rule as atb_bfp16_quantize;
- *                   rows are fully written including their zero padding.
+ *                   the tail of the last panel (columns N .. 64 * panels - 1) is
+ *                   written as zero, so the buffer is a valid operand as it is.
  * c_format BFP16 needs N % 8 == 0 (whole blocks; else ATB_ERR_INVALID_ARG);
  * formats other than (BF16, BF16) need an instance that carries the variants: all but (32, 256, 64, 256) and
  * (32, 256, 128, 256) (else ATB_ERR_BAD_TILE).  All else as atb_gemm_create. */
@@ -127,10 +131,12 @@ atb_status atb_instance_get(int index, int *T_MA, int *T_MC, int *T_K, int *T_N)
 /* ----------------------------------------------------------------- BFP16 */
 
 typedef struct atb_bfp16_layout_t {
-    int64_t ldm;      /* bytes between mantissa rows */
-    int64_t lde;      /* bytes between exponent rows */
-    int64_t exp_off;  /* byte offset of the exponent plane */
-    int64_t bytes;    /* total size of the buffer */
+    int64_t panel_k;     /* K extent of a panel: 64 */
+    int64_t panels;      /* ceil(K / 64) */
+    int64_t man_stride;  /* bytes between panels of the mantissa plane: M * 64 */
+    int64_t exp_stride;  /* bytes between panels of the exponent plane: M * 8 */
+    int64_t exp_off;     /* byte offset of the exponent plane */
+    int64_t bytes;       /* total size of the buffer */
 } atb_bfp16_layout_t;
 
 /* Layout of an A_bfp buffer for an M x K matrix (K % 8 == 0). */

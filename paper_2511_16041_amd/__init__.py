@@ -57,8 +57,8 @@ class MicroModel(ctypes.Structure):
 
 
 class Bfp16Layout(ctypes.Structure):
-    _fields_ = [("ldm", ctypes.c_int64), ("lde", ctypes.c_int64),
-                ("exp_off", ctypes.c_int64), ("bytes", ctypes.c_int64)]
+    _fields_ = [("panel_k", ctypes.c_int64), ("panels", ctypes.c_int64), ("man_stride", ctypes.c_int64),
+                ("exp_stride", ctypes.c_int64), ("exp_off", ctypes.c_int64), ("bytes", ctypes.c_int64)]
 
 
 # every symbol include/atb.h declares
@@ -151,6 +151,34 @@ def bfp16_layout(M: int, K: int) -> Bfp16Layout:
 
 def bfp16_bytes(M: int, K: int) -> int:
     return int(lib().atb_bfp16_bytes(M, K))
+
+
+def bfp16_pack_host(mant, expo):
+    """Host-side layout marshalling (numpy, no arithmetic): (int8 [M][K], uint8 [M][K/8]) -> the uint8
+    buffer atb_bfp16_layout(M, K) describes (K-panel-major planes, zero padding)."""
+    import numpy as np
+    M, K = mant.shape
+    lay = bfp16_layout(M, K)
+    P, pk = int(lay.panels), int(lay.panel_k)
+    buf = np.zeros(lay.bytes, dtype=np.uint8)
+    mp = np.zeros((M, P * pk), dtype=np.uint8)
+    mp[:, :K] = np.ascontiguousarray(mant).view(np.uint8)
+    buf[: P * M * pk] = mp.reshape(M, P, pk).transpose(1, 0, 2).reshape(-1)
+    ep = np.zeros((M, P * pk // 8), dtype=np.uint8)
+    ep[:, : K // 8] = expo
+    buf[lay.exp_off: lay.exp_off + P * M * (pk // 8)] = ep.reshape(M, P, pk // 8).transpose(1, 0, 2).reshape(-1)
+    return buf
+
+
+def bfp16_unpack_host(buf, M: int, K: int):
+    """Inverse of bfp16_pack_host: (mant int8 [M][K], expo uint8 [M][K/8], the mantissa bytes of the
+    last panel's tail [M][64 * panels - K], which the layout requires to be zero)."""
+    import numpy as np
+    lay = bfp16_layout(M, K)
+    P, pk = int(lay.panels), int(lay.panel_k)
+    mp = np.asarray(buf[: P * M * pk]).reshape(P, M, pk).transpose(1, 0, 2).reshape(M, P * pk)
+    ep = np.asarray(buf[lay.exp_off: lay.exp_off + P * M * (pk // 8)]).reshape(P, M, pk // 8).transpose(1, 0, 2).reshape(M, P * pk // 8)
+    return mp[:, :K].view(np.int8).copy(), ep[:, : K // 8].copy(), mp[:, K:].copy()
 
 
 def hw_params(which: str = "mi355x") -> HwParams:

@@ -62,10 +62,12 @@ extern "C" atb_status atb_instance_get(int index, int *T_MA, int *T_MC, int *T_K
 extern "C" atb_status atb_bfp16_layout(int64_t M, int64_t K, atb_bfp16_layout_t *out)
 {
     if (!out || M < 1 || K < 8 || (K % 8) != 0) return ATB_ERR_INVALID_ARG;
-    out->ldm = atb::round_up(K, 128);
-    out->lde = out->ldm / 8;
-    out->exp_off = atb::round_up(M * out->ldm, 256);
-    out->bytes = atb::round_up(out->exp_off + M * out->lde, 256);
+    out->panel_k = atb::kPanelK;
+    out->panels = (K + atb::kPanelK - 1) / atb::kPanelK;
+    out->man_stride = M * atb::kPanelK;
+    out->exp_stride = M * (atb::kPanelK / 8);
+    out->exp_off = atb::round_up(out->panels * out->man_stride, 256);
+    out->bytes = atb::round_up(out->exp_off + out->panels * out->exp_stride, 256);
     return ATB_OK;
 }
 
@@ -82,10 +84,10 @@ extern "C" atb_status atb_bfp16_quantize(const float *A, int64_t lda, void *A_bf
     atb_bfp16_layout_t l;
     if (!A || !A_bfp || atb_bfp16_layout(M, K, &l) != ATB_OK || lda < K || (lda % 4) != 0) return ATB_ERR_INVALID_ARG;
     if (!aligned16(A) || !aligned16(A_bfp)) return ATB_ERR_INVALID_ARG;
-    if (M * (l.ldm / 16) > (int64_t)0x7FFFFFFF * 256) return ATB_ERR_INVALID_ARG;
+    if (M * l.panels * 4 > (int64_t)0x7FFFFFFF * 256) return ATB_ERR_INVALID_ARG;
     int8_t *Am = static_cast<int8_t *>(A_bfp);
     uint8_t *Ae = static_cast<uint8_t *>(A_bfp) + l.exp_off;
-    return hip_status(atb::launch_quantize(A, lda, Am, Ae, M, K, l.ldm, l.lde, static_cast<hipStream_t>(stream)));
+    return hip_status(atb::launch_quantize(A, lda, Am, Ae, M, K, static_cast<hipStream_t>(stream)));
 }
 
 extern "C" atb_status atb_bfp16_decode(const void *A_bfp, void *A_bf16, int64_t M, int64_t K, void *stream)
@@ -95,8 +97,7 @@ extern "C" atb_status atb_bfp16_decode(const void *A_bfp, void *A_bf16, int64_t 
     if (!aligned16(A_bfp) || !aligned16(A_bf16)) return ATB_ERR_INVALID_ARG;
     const int8_t *Am = static_cast<const int8_t *>(A_bfp);
     const uint8_t *Ae = static_cast<const uint8_t *>(A_bfp) + l.exp_off;
-    return hip_status(atb::launch_decode(Am, Ae, static_cast<uint16_t *>(A_bf16), M, K, l.ldm, l.lde,
-                                         static_cast<hipStream_t>(stream)));
+    return hip_status(atb::launch_decode(Am, Ae, static_cast<uint16_t *>(A_bf16), M, K, static_cast<hipStream_t>(stream)));
 }
 
 extern "C" atb_status atb_gemm_create(atb_gemm **out, int64_t M, int64_t N, int64_t K,
@@ -116,11 +117,11 @@ extern "C" atb_status atb_gemm_create_fmt(atb_gemm **out, int64_t M, int64_t N, 
         return ATB_ERR_INVALID_ARG;
     const bool other_fmt = (b_format != ATB_FMT_BF16 || c_format != ATB_FMT_BF16);
     if (c_format == ATB_FMT_BFP16 && (N % 8) != 0) return ATB_ERR_INVALID_ARG;   // whole blocks along N
-    if (N * atb::round_up(K, 128) >= ((int64_t)1 << 31) || M * atb::round_up(N, 128) >= ((int64_t)1 << 31))
+    if (N * atb::round_up(K, 64) >= ((int64_t)1 << 31) || M * atb::round_up(N, 64) >= ((int64_t)1 << 31))
         return ATB_ERR_INVALID_ARG;
     // 32-bit element offsets inside the kernel: keep every plane below 2^31 elements
-    if (M > (1 << 24) || N > (1 << 24) || K > (1 << 24) || M * N >= ((int64_t)1 << 31) ||
-        M * atb::round_up(K, 128) >= ((int64_t)1 << 31) || K * N >= ((int64_t)1 << 31))
+    if (M > (1 << 23) || N > (1 << 23) || K > (1 << 24) || M * N >= ((int64_t)1 << 31) ||
+        M * atb::round_up(K, 64) >= ((int64_t)1 << 31) || K * N >= ((int64_t)1 << 31))
         return ATB_ERR_INVALID_ARG;
     if (T_MA < 1 || T_MC < 1 || T_K < 1 || T_N < 1) return ATB_ERR_INVALID_ARG;
     if (T_MC % T_MA != 0) return ATB_ERR_BAD_TILE;
@@ -140,21 +141,19 @@ extern "C" atb_status atb_gemm_create_fmt(atb_gemm **out, int64_t M, int64_t N, 
     g->c_format = (int)c_format;
     atb_bfp16_layout(M, K, &g->layout);
     atb_bfp16_layout(N, K, &g->layout_b);
-    g->layout_c = atb_bfp16_layout_t{0, 0, 0, 0};
+    g->layout_c = atb_bfp16_layout_t{0, 0, 0, 0, 0, 0};
     if (c_format == ATB_FMT_BFP16) atb_bfp16_layout(M, N, &g->layout_c);
     atb::GemmParams &p = g->proto;
     p.Am = nullptr; p.Ae = nullptr; p.B = nullptr; p.C = nullptr;
     p.Bm = nullptr; p.Be = nullptr; p.Cm = nullptr; p.Ce = nullptr;
-    p.ldbm = (int)g->layout_b.ldm; p.ldbe = (int)g->layout_b.lde;
-    p.ldcm = (int)g->layout_c.ldm; p.ldce = (int)g->layout_c.lde;
+    p.k_panels = (int)g->layout.panels;
+    p.n_panels = (int)g->layout_c.panels;
     p.M = (int)M; p.N = (int)N; p.K = (int)K;
-    p.ldm = (int)g->layout.ldm;
-    p.lde = (int)g->layout.lde;
     p.tiles_m = (int)((M + T_MC - 1) / T_MC);
     p.tiles_n = (int)((N + T_N - 1) / T_N);
-    // C in BFP16: the tiles also cover the zero padding of the C rows (N .. ldcm - 1), so that the
-    // result can be the BFP16 operand of a following GEMM as it is
-    if (c_format == ATB_FMT_BFP16) p.tiles_n = (int)((atb::round_up(N, 128) + T_N - 1) / T_N);
+    // C in BFP16: the tiles also cover the zero tail of C's last panel (columns N .. 64 * panels - 1),
+    // so that the result can be the BFP16 operand of a following GEMM as it is
+    if (c_format == ATB_FMT_BFP16) p.tiles_n = (int)((atb::round_up(N, atb::kPanelK) + T_N - 1) / T_N);
     p.group_m = (int)std::max<int64_t>(1, 2048 / T_MC);   // an XCD's patch of C tiles is 2048 rows high
     *out = g;
     return ATB_OK;

@@ -6,8 +6,8 @@
 //       for normal x; fp32 subnormals and zeros contribute 0),
 //   m = clamp(round_to_nearest_even(x * 2^(133 - E)), -127, 127),
 //   value = m * 2^(E - 133).
-// Both kernels are HBM-bound streaming kernels: 16 elements per lane, 16-byte
-// accesses, consecutive lanes on consecutive addresses.
+// Both kernels are HBM-bound streaming kernels: 16 elements per lane, 16-byte accesses.  The BFP16
+// buffer is K-panel-major (see include/atb.h): [panel of 64 k][row][64] mantissas, [panel][row][8] exponents.
 #include "atb_internal.h"
 
 namespace atb {
@@ -36,11 +36,15 @@ __device__ __forceinline__ void quantize_block(const float (&x)[8], unsigned &E,
     w1 = (int)(b[4] | (b[5] << 8) | (b[6] << 16) | (b[7] << 24));
 }
 
+// One lane per 16 consecutive k of a row (two BFP16 blocks).  Lanes run along K within a row, so the
+// fp32 reads are contiguous; the writes land in the K-panel-major layout: 4 neighbouring lanes fill
+// the 64 mantissa bytes and 8 exponent bytes of one (panel, row).  Chunks beyond K (the tail of the
+// last panel) are written as zero.
 __global__ void __launch_bounds__(256) quantize_kernel(const float *__restrict__ A, int64_t lda,
                                                        int8_t *__restrict__ Am, uint8_t *__restrict__ Ae,
-                                                       int64_t M, int64_t K, int64_t ldm, int64_t lde)
+                                                       int64_t M, int64_t K, int64_t panels)
 {
-    const int64_t chunks_per_row = ldm / 16;
+    const int64_t chunks_per_row = panels * (kPanelK / 16);
     const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= M * chunks_per_row) return;
     const int64_t row = c / chunks_per_row, q = c % chunks_per_row;
@@ -65,23 +69,21 @@ __global__ void __launch_bounds__(256) quantize_kernel(const float *__restrict__
     int4 m;
     quantize_block(lo, E0, m.x, m.y);
     quantize_block(hi, E1, m.z, m.w);
-    *reinterpret_cast<int4 *>(Am + row * ldm + k0) = m;
-    *reinterpret_cast<unsigned short *>(Ae + row * lde + (k0 >> 3)) = (unsigned short)(E0 | (E1 << 8));
-    // zero the unused tail of the exponent row
-    if (q == 0)
-        for (int64_t j = ldm / 8; j < lde; ++j) Ae[row * lde + j] = 0;
+    const int64_t panel = k0 / kPanelK, kin = k0 % kPanelK;
+    *reinterpret_cast<int4 *>(Am + (panel * M + row) * kPanelK + kin) = m;
+    *reinterpret_cast<unsigned short *>(Ae + (panel * M + row) * (kPanelK / 8) + (kin >> 3)) = (unsigned short)(E0 | (E1 << 8));
 }
 
 __global__ void __launch_bounds__(256) decode_kernel(const int8_t *__restrict__ Am, const uint8_t *__restrict__ Ae,
-                                                     uint16_t *__restrict__ out, int64_t M, int64_t K,
-                                                     int64_t ldm, int64_t lde)
+                                                     uint16_t *__restrict__ out, int64_t M, int64_t K)
 {
     const int64_t blocks_per_row = K / 8;
     const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= M * blocks_per_row) return;
     const int64_t row = c / blocks_per_row, kb = c % blocks_per_row;
-    const int2 w = *reinterpret_cast<const int2 *>(Am + row * ldm + kb * 8);
-    const int shift = (int)Ae[row * lde + kb] - 133;
+    const int64_t panel = (kb * 8) / kPanelK, bin = kb % (kPanelK / 8);
+    const int2 w = *reinterpret_cast<const int2 *>(Am + (panel * M + row) * kPanelK + bin * 8);
+    const int shift = (int)Ae[(panel * M + row) * (kPanelK / 8) + bin] - 133;
     bf16x8 r;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
@@ -95,22 +97,23 @@ __global__ void __launch_bounds__(256) decode_kernel(const int8_t *__restrict__ 
 }  // namespace
 
 hipError_t launch_quantize(const float *A, int64_t lda, int8_t *Am, uint8_t *Ae, int64_t M, int64_t K,
-                           int64_t ldm, int64_t lde, hipStream_t stream)
+                           hipStream_t stream)
 {
-    const int64_t n = M * (ldm / 16);
+    const int64_t panels = (K + kPanelK - 1) / kPanelK;
+    const int64_t n = M * panels * (kPanelK / 16);
     if (n == 0) return hipSuccess;
     const int64_t blocks = (n + 255) / 256;
-    hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, A, lda, Am, Ae, M, K, ldm, lde);
+    hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, A, lda, Am, Ae, M, K, panels);
     return hipGetLastError();
 }
 
 hipError_t launch_decode(const int8_t *Am, const uint8_t *Ae, uint16_t *out, int64_t M, int64_t K,
-                         int64_t ldm, int64_t lde, hipStream_t stream)
+                         hipStream_t stream)
 {
     const int64_t n = M * (K / 8);
     if (n == 0) return hipSuccess;
     const int64_t blocks = (n + 255) / 256;
-    hipLaunchKernelGGL(decode_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, Am, Ae, out, M, K, ldm, lde);
+    hipLaunchKernelGGL(decode_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, Am, Ae, out, M, K);
     return hipGetLastError();
 }
 

@@ -102,7 +102,7 @@ struct Shape {
     static_assert(T_MC % T_MA == 0, "rho must be an integer");
     static_assert(KU % 2 == 0 && PF >= 2 && (KU * RHO) % PF == 0, "prefetch distance: at least 2 (fetch and decode overlap), dividing the sub-tiles of one loop iteration");
     static_assert(AB == 2 || (AB == 4 && PF >= 3 && (KU * RHO) % 4 == 0), "4 A buffers need a fetch distance of 3 or more and must divide the sub-tiles of one loop iteration");
-    static_assert(128 % T_K == 0 && T_K % 32 == 0, "T_K must divide the 128-byte row padding of the mantissa plane; exponent dwords stay aligned");
+    static_assert(T_K % 64 == 0, "a K-step is a whole number of 64-wide panels of the BFP16 layout");
     static_assert(T_MA % 32 == 0 && T_N % (32 * WN) == 0 && T_K % 16 == 0, "MFMA 32x32x16 granularity");
     static_assert(MT % WM == 0 && SMT % WM == 0, "every sub-tile must feed every wave row equally");
     static_assert(A_CHUNKS % NTS == 0 && NTS % A_CPR == 0, "A staging must split evenly over the threads");
@@ -205,7 +205,6 @@ struct TileKernel {
     static constexpr int B_BYTES = BBFP ? S::BT_BYTES : S::B_BYTES;
     static_assert(!BBFP || (NPAIR_B % S::RHO == 0 && S::T_K % 16 == 0 && (S::T_N * S::T_K / 16) % NTS == 0), "BFP16 B staging must split evenly");
     static_assert(!BBFP || S::LDS_BYTES_BT <= 160 * 1024, "LDS budget of a gfx950 CU");
-    static_assert(!BBFP || S::KU * S::T_K <= 128, "a loop body of K-steps must stay inside the 128-byte row padding of both mantissa planes");
     static_assert((ROLE == 0) == (S::NT != 512), "two wave groups exactly when two waves share a SIMD");
 
     const GemmParams &p;
@@ -217,7 +216,7 @@ struct TileKernel {
     char *b_req[2];                    // LDS byte address of this wave's first 1 KiB B request, per buffer
     // Byte offsets of this thread's global loads relative to the current K-step.  They never
     // change: the K-step advance is applied to the (scalar) buffer descriptors instead, base up and
-    // size down, so the hardware range check keeps masking rows >= M of A and rows >= K of B, and no
+    // size down, so the hardware range check keeps masking panels past the last of A and rows >= K of B, and no
     // vector register that a memory instruction has just read is written right after it.
     int a_moff[S::RHO][APTN], a_eoff[S::RHO][APTN], b_off[BPTN];
     int b_col[BPTN];        // first column of request i's chunk (only used when !VEC)
@@ -256,7 +255,7 @@ struct TileKernel {
         wn = wave / S::WM;
         const int stid = tid % NTS;                  // index within the threads that share this staging job
         const int a_row = stid / A_CPR, a_q = stid % A_CPR;
-        e_shift = ((a_q * (ACE / 8)) & 3) * 8;
+        e_shift = ((((a_q * ACE) % kPanelK) / 8) & 3) * 8;
         // B staging.  The tile is row-major in LDS ([k][n], no padding), cut into slabs of NTS
         // 16-byte slots.  Request i of this wave group fills slab B_FIRST + i: wave w of the group
         // the 1 KiB at slot 64 w of the slab, lane l the slot l of that.  Chunk c of row k is stored at chunk position c ^ ((k & 3) << SWZ) of its row, so
@@ -287,14 +286,14 @@ struct TileKernel {
         }
         am_ptr = p.Am;
         ae_ptr = p.Ae;
-        am_left = p.M * p.ldm;
-        ae_left = p.M * p.lde;
+        am_left = p.k_panels * p.M * kPanelK;
+        ae_left = p.k_panels * p.M * (kPanelK / 8);
         remake_a();
         if constexpr (BBFP) {
             // staging: thread -> (row n = stid / 4 + 64 i, chunk q = stid % 4 ... ) for T_K = 64; in general T_K / 16 chunks per row
             constexpr int CPR = S::T_K / 16;
             const int b_row = stid / CPR, b_q = stid % CPR;
-            eb_shift = ((b_q * 2) & 3) * 8;
+            eb_shift = ((((b_q * 16) % kPanelK) / 8) & 3) * 8;
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
                 char *b_base = lds + S::AB * S::A_BYTES + b * B_BYTES;
@@ -304,31 +303,35 @@ struct TileKernel {
             }
             bm_ptr = p.Bm;
             be_ptr = p.Be;
-            bm_left = p.N * p.ldbm;
-            be_left = p.N * p.ldbe;
+            bm_left = p.k_panels * p.N * kPanelK;
+            be_left = p.k_panels * p.N * (kPanelK / 8);
             remake_bt();
             // rows >= N of B^T lie beyond the end of the planes and read as zero
 #pragma unroll
             for (int i = 0; i < BTPT; ++i) {
                 const int grow = n0 + b_row + i * (NTS / CPR);
-                bt_moff[i] = grow * p.ldbm + b_q * 16;
-                bt_eoff[i] = grow * p.ldbe + ((b_q * 2) & ~3);
+                const int pnl = (b_q * 16) / kPanelK, kin = (b_q * 16) % kPanelK;
+                bt_moff[i] = (pnl * p.N + grow) * kPanelK + kin;
+                bt_eoff[i] = (pnl * p.N + grow) * (kPanelK / 8) + ((kin / 8) & ~3);
             }
         } else {
             b_ptr = p.B;
             b_left = p.K * p.N * 2;
             remake_b();
         }
-        // Offsets of sub-tile 0 / K-step 0.  Rows >= M lie beyond the end of the planes and read as
-        // zero; k never leaves a row because ldm is a multiple of 128 and of T_K (the mantissa bytes
-        // between K and ldm are zero by the layout's contract).
+        // Offsets of sub-tile 0 / K-step 0 in the K-panel-major planes: the chunks of a sub-tile follow
+        // each other in memory in the order of the staging threads, so a wave's request is one
+        // contiguous KiB.  Rows >= M run into the next panel's rows (or past the end of the plane, which
+        // reads as zero): they only feed rows of C that are never stored.  The tail of the last panel
+        // (k >= K) is zero by the layout's contract, panels past the last read as zero.
 #pragma unroll
         for (int sub = 0; sub < S::RHO; ++sub)
 #pragma unroll
             for (int i = 0; i < APT; ++i) {
                 const int grow = m0 + sub * S::T_MA + a_row + (A_FIRST + i) * (NTS / A_CPR);
-                a_moff[sub][i] = grow * p.ldm + a_q * ACE;
-                a_eoff[sub][i] = grow * p.lde + ((a_q * (ACE / 8)) & ~3);
+                const int pnl = (a_q * ACE) / kPanelK, kin = (a_q * ACE) % kPanelK;
+                a_moff[sub][i] = (ATB_ABLATE & 4096) ? (stid + NTS * (sub * APT + i)) * 16 : (pnl * p.M + grow) * kPanelK + kin;
+                a_eoff[sub][i] = (ATB_ABLATE & 2048) ? stid * 4 : (pnl * p.M + grow) * (kPanelK / 8) + ((kin / 8) & ~3);
             }
         // B rows >= K lie beyond the end of B and read as zero; columns >= N wrap into the next row
         // and only feed output columns that are never stored.
@@ -381,10 +384,10 @@ struct TileKernel {
         bt_mant[set][i] = __builtin_amdgcn_raw_buffer_load_b128(rs.bm, bt_moff[i], 0, 0);
         bt_expo[set][i] = __builtin_amdgcn_raw_buffer_load_b32(rs.be, bt_eoff[i], 0, 0);
         if constexpr (i == BTPT - 1) {
-            bm_ptr += S::T_K;
-            be_ptr += S::T_K / 8;
-            bm_left = max(bm_left - S::T_K, 0);
-            be_left = max(be_left - S::T_K / 8, 0);
+            bm_ptr += (S::T_K / kPanelK) * p.N * kPanelK;
+            be_ptr += (S::T_K / kPanelK) * p.N * (kPanelK / 8);
+            bm_left = max(bm_left - (S::T_K / kPanelK) * p.N * kPanelK, 0);
+            be_left = max(be_left - (S::T_K / kPanelK) * p.N * (kPanelK / 8), 0);
             remake_bt();
         }
     }
@@ -412,10 +415,10 @@ struct TileKernel {
         // the aligned dword that holds this chunk's exponent byte(s): sub-dword loads are far slower
         if constexpr (!(ATB_ABLATE & 1024)) a_expo[set][i] = __builtin_amdgcn_raw_buffer_load_b32(rs.ae, a_eoff[sub][i], 0, 0);
         if constexpr (sub == S::RHO - 1 && i == APT - 1 && !(ATB_ABLATE & 128)) {
-            am_ptr += S::T_K;
-            ae_ptr += S::T_K / 8;
-            am_left = max(am_left - S::T_K, 0);
-            ae_left = max(ae_left - S::T_K / 8, 0);
+            am_ptr += (S::T_K / kPanelK) * p.M * kPanelK;
+            ae_ptr += (S::T_K / kPanelK) * p.M * (kPanelK / 8);
+            am_left = max(am_left - (S::T_K / kPanelK) * p.M * kPanelK, 0);
+            ae_left = max(ae_left - (S::T_K / kPanelK) * p.M * (kPanelK / 8), 0);
             remake_a();
         }
     }
@@ -807,7 +810,7 @@ struct TileKernel {
     // Epilogue for C in BFP16 (blocks of 8 along N): a block is the 4 consecutive columns of lane l
     // plus the 4 of lane l ^ 32 (same row).  Same arithmetic as the stand-alone quantiser: shared
     // exponent = largest fp32 exponent field, mantissa = clamp(rne(x * 2^(133 - E)), +-127).
-    // Needs N % 8 == 0; columns N .. ldcm - 1 (the row padding of the layout) are written as zero.
+    // Needs N % 8 == 0; columns N .. 64 * n_panels - 1 (the tail of C's last panel) are written as zero.
     ATB_DEV void store_c_bfp()
     {
 #pragma unroll
@@ -837,9 +840,10 @@ struct TileKernel {
                         r = fminf(fmaxf(r, -127.0f), 127.0f);
                         w |= ((unsigned)((int)r) & 0xFFu) << (8 * t);
                     }
-                    if (m < p.M && n < p.ldcm) {
-                        *reinterpret_cast<unsigned *>(p.Cm + (int64_t)m * p.ldcm + n) = w;
-                        if ((lane >> 5) == 0) p.Ce[(int64_t)m * p.ldce + (n >> 3)] = (uint8_t)e;
+                    if (m < p.M && n < p.n_panels * kPanelK) {
+                        const int64_t rec = (int64_t)(n / kPanelK) * p.M + m;       // (panel, row)
+                        *reinterpret_cast<unsigned *>(p.Cm + rec * kPanelK + n % kPanelK) = w;
+                        if ((lane >> 5) == 0) p.Ce[rec * (kPanelK / 8) + ((n % kPanelK) >> 3)] = (uint8_t)e;
                     }
                 }
             }

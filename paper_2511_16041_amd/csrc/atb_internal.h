@@ -11,17 +11,17 @@ namespace atb {
 
 // Arguments of one GEMM launch (device pointers are never dereferenced on the host).
 struct GemmParams {
-    const int8_t *Am;    // mantissa plane  [M][ldm]
-    const uint8_t *Ae;   // exponent plane  [M][lde]
+    const int8_t *Am;    // mantissa plane  [panels][M][64]
+    const uint8_t *Ae;   // exponent plane  [panels][M][8]
     const uint16_t *B;   // bf16 [K][N]                              (B in bf16)
     uint16_t *C;         // bf16 [M][N]                              (C in bf16)
-    const int8_t *Bm;    // mantissa plane of B^T  [N][ldbm]         (B in BFP16, blocks along K)
-    const uint8_t *Be;   // exponent plane of B^T  [N][ldbe]
-    int8_t *Cm;          // mantissa plane of C    [M][ldcm]         (C in BFP16, blocks along N)
-    uint8_t *Ce;         // exponent plane of C    [M][ldce]
+    const int8_t *Bm;    // mantissa plane of B^T  [panels][N][64]   (B in BFP16, blocks along K)
+    const uint8_t *Be;   // exponent plane of B^T  [panels][N][8]
+    int8_t *Cm;          // mantissa plane of C    [panels of N][M][64]   (C in BFP16, blocks along N)
+    uint8_t *Ce;         // exponent plane of C    [panels of N][M][8]
     int M, N, K;
-    int ldm, lde;
-    int ldbm, ldbe, ldcm, ldce;
+    int k_panels;        // ceil(K / 64): panels of A (and of B^T)
+    int n_panels;        // ceil(N / 64): panels of C when it is BFP16
     int tiles_m, tiles_n;   // number of C tiles along M and N
     int group_m;            // tile rows that are walked together (rasterisation)
 };
@@ -45,9 +45,10 @@ const Instance &instance(int i);
 int find_instance(int T_MA, int T_MC, int T_K, int T_N);
 
 hipError_t launch_quantize(const float *A, int64_t lda, int8_t *Am, uint8_t *Ae, int64_t M, int64_t K,
-                           int64_t ldm, int64_t lde, hipStream_t stream);
+                           hipStream_t stream);
 hipError_t launch_decode(const int8_t *Am, const uint8_t *Ae, uint16_t *out, int64_t M, int64_t K,
-                         int64_t ldm, int64_t lde, hipStream_t stream);
+                         hipStream_t stream);
+constexpr int kPanelK = 64;      // K extent of a panel of the BFP16 layout
 
 static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 

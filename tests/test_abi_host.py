@@ -2,6 +2,8 @@
 declares, validates arguments without touching a device, lays BFP16 out as
 documented, and its model / selector agree with the oracle of the paper's model."""
 import ctypes
+
+import numpy as np
 import os
 import re
 
@@ -68,10 +70,10 @@ def test_instances_and_create_validation():
 def test_bfp16_layout():
     for (M, K) in [(256, 256), (3000, 4104), (1, 8), (7, 24)]:
         lay = atb.bfp16_layout(M, K)
-        assert lay.ldm % 128 == 0 and K <= lay.ldm < K + 128
-        assert lay.lde == lay.ldm // 8
-        assert lay.exp_off % 256 == 0 and lay.exp_off >= M * lay.ldm
-        assert lay.bytes % 256 == 0 and lay.bytes >= lay.exp_off + M * lay.lde
+        assert lay.panel_k == 64 and lay.panels == (K + 63) // 64
+        assert lay.man_stride == M * 64 and lay.exp_stride == M * 8
+        assert lay.exp_off % 256 == 0 and lay.exp_off >= lay.panels * lay.man_stride
+        assert lay.bytes % 256 == 0 and lay.bytes >= lay.exp_off + lay.panels * lay.exp_stride
         assert atb.bfp16_bytes(M, K) == lay.bytes
     assert atb.bfp16_bytes(4, 12) == 0 and atb.bfp16_bytes(0, 8) == 0
     # 9 bytes per 8 elements, up to padding
@@ -219,3 +221,17 @@ def test_microkernel_model_against_measurements():
     mm = atb.MicroModel()
     assert L.atb_model_microkernel(96, 256, 64, 256, 2, 4, 1, ctypes.byref(mm)) == 2      # rho not an integer
     assert L.atb_model_microkernel(128, 256, 64, 256, 3, 4, 1, ctypes.byref(mm)) == 2     # bands do not divide
+
+
+def test_host_packers_agree():
+    """The binding's layout marshalling against the tests' own packer (written from include/atb.h)."""
+    from helpers import pack_a_bfp, unpack_a_bfp
+    rng = np.random.default_rng(0)
+    for (M, K) in [(5, 8), (37, 72), (64, 64), (130, 200)]:
+        mant = rng.integers(-127, 128, size=(M, K), dtype=np.int8)
+        expo = rng.integers(0, 255, size=(M, K // 8), dtype=np.uint8)
+        a, b = pack_a_bfp(mant, expo), atb.bfp16_pack_host(mant, expo)
+        assert np.array_equal(a, b)
+        for unpack in (unpack_a_bfp, atb.bfp16_unpack_host):
+            m2, e2, pad = unpack(a, M, K)
+            assert np.array_equal(m2, mant) and np.array_equal(e2, expo) and not pad.any()
