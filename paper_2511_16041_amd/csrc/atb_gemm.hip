@@ -128,7 +128,9 @@ constexpr int kOutOfRange = (int)0x80000000;     // a byte offset no buffer of o
 
 #define ATB_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-// Developer ablation switches (timing experiments only; results are wrong when non-zero):
+// Developer ablation switches (timing experiments only; results are wrong when non-zero, and since the
+// chip is power-limited and its power depends on the data, a switch that changes the operand values,
+// e.g. by decoding stale registers, overstates what the removed work costs):
 // 2 B fragments read once, 8 no LDS stores of decoded A, 16 no A-fragment reads after the first band,
 // 32 no MFMA, 64 no barrier, 128 global loads never advance (always the first K-step: cache-hot),
 // 256 no A loads, 512 no bf16 B loads, 1024 no exponent loads.
@@ -195,6 +197,10 @@ struct TileKernel {
     static constexpr int A_FIRST = (ROLE == 2) ? AO : 0;                                 // first A slab of this wave group
     static constexpr int APT = (ROLE == 0) ? S::A_SLABS : (ROLE == 1) ? AO : S::A_SLABS - AO;   // A chunks per thread per sub-tile
     static constexpr int NPAIR = APT * ACE / 2;                                          // mantissa pairs per thread per sub-tile
+    // A thread with two 16-mantissa chunks takes them side by side in one row (32 consecutive k): their
+    // four exponent bytes are one aligned dword, so one exponent request serves both chunks.
+    static constexpr bool PAIRK = (APT == 2 && ACE == 16 && A_FIRST == 0 && S::T_K == 64);
+    static constexpr int A_VMEM = PAIRK ? 3 : APT * 2;       // memory requests per thread and A sub-tile
     static constexpr int B_FIRST = (ROLE == 2) ? S::BO : 0;
     static constexpr int BPT = BBFP ? 0 : (ROLE == 0) ? S::B_SLABS : (ROLE == 1) ? S::BO : S::B_SLABS - S::BO;   // bf16 B chunks per thread per tile
     static constexpr int BTPT = !BBFP ? 0 : (ROLE == 1) ? 0 : S::BT_SLABS;               // BFP16 B chunks (16 mantissas) per thread per tile
@@ -254,7 +260,8 @@ struct TileKernel {
         wm = wave % S::WM;
         wn = wave / S::WM;
         const int stid = tid % NTS;                  // index within the threads that share this staging job
-        const int a_row = stid / A_CPR, a_q = stid % A_CPR;
+        const int a_row = PAIRK ? stid / 2 : stid / A_CPR;
+        const int a_q = PAIRK ? 2 * (stid % 2) : stid % A_CPR;           // first chunk of this thread in its row
         e_shift = ((((a_q * ACE) % kPanelK) / 8) & 3) * 8;
         // B staging.  The tile is row-major in LDS ([k][n], no padding), cut into slabs of NTS
         // 16-byte slots.  Request i of this wave group fills slab B_FIRST + i: wave w of the group
@@ -328,10 +335,11 @@ struct TileKernel {
         for (int sub = 0; sub < S::RHO; ++sub)
 #pragma unroll
             for (int i = 0; i < APT; ++i) {
-                const int grow = m0 + sub * S::T_MA + a_row + (A_FIRST + i) * (NTS / A_CPR);
-                const int pnl = (a_q * ACE) / kPanelK, kin = (a_q * ACE) % kPanelK;
-                a_moff[sub][i] = (ATB_ABLATE & 4096) ? (stid + NTS * (sub * APT + i)) * 16 : (pnl * p.M + grow) * kPanelK + kin;
-                a_eoff[sub][i] = (ATB_ABLATE & 2048) ? stid * 4 : (pnl * p.M + grow) * (kPanelK / 8) + ((kin / 8) & ~3);
+                const int grow = m0 + sub * S::T_MA + a_row + (PAIRK ? 0 : (A_FIRST + i) * (NTS / A_CPR));
+                const int cq = PAIRK ? a_q + i : a_q;                  // chunk index within the row
+                const int pnl = (cq * ACE) / kPanelK, kin = (cq * ACE) % kPanelK;
+                a_moff[sub][i] = (pnl * p.M + grow) * kPanelK + kin;
+                a_eoff[sub][i] = (pnl * p.M + grow) * (kPanelK / 8) + ((kin / 8) & ~3);
             }
         // B rows >= K lie beyond the end of B and read as zero; columns >= N wrap into the next row
         // and only feed output columns that are never stored.
@@ -413,7 +421,8 @@ struct TileKernel {
             a_mant[set][i] = intx4{t.x, t.y, 0, 0};
         }
         // the aligned dword that holds this chunk's exponent byte(s): sub-dword loads are far slower
-        if constexpr (!(ATB_ABLATE & 1024)) a_expo[set][i] = __builtin_amdgcn_raw_buffer_load_b32(rs.ae, a_eoff[sub][i], 0, 0);
+        if constexpr (!(ATB_ABLATE & 1024) && (!PAIRK || i == 0))
+            a_expo[set][i] = __builtin_amdgcn_raw_buffer_load_b32(rs.ae, a_eoff[sub][i], 0, 0);
         if constexpr (sub == S::RHO - 1 && i == APT - 1 && !(ATB_ABLATE & 128)) {
             am_ptr += (S::T_K / kPanelK) * p.M * kPanelK;
             ae_ptr += (S::T_K / kPanelK) * p.M * (kPanelK / 8);
@@ -509,7 +518,7 @@ struct TileKernel {
             pk.v = bf16x2{(__bf16)ldf[(u - 2) % 2][0], (__bf16)ldf[(u - 2) % 2][1]};
             dec[t % 4] = pk.w;
             if constexpr (t % 4 == 3) {
-                char *dst = dst_base + i * ROWS * S::PA + (t / 4) * 16;
+                char *dst = dst_base + ((!ISB && PAIRK) ? i * (ACE * 2) : i * ROWS * S::PA) + (t / 4) * 16;
                 if constexpr (ATB_ABLATE & 8)
                     asm volatile("" ::"v"(dec[0]), "v"(dec[1]), "v"(dec[2]), "v"(dec[3]));
                 else
@@ -519,8 +528,9 @@ struct TileKernel {
         if constexpr (u >= 1 && u - 1 < count) {
             constexpr int j = first + u - 1, i = j / PPC, t = j % PPC;
             if constexpr (t % 4 == 0 || u == 1) {
-                const unsigned e = ISB ? bt_expo[set][i] : a_expo[set][i];
-                shift = (int)((e >> ((ISB ? eb_shift : e_shift) + 8 * (t / 4))) & 0xFFu) - 133;
+                const unsigned e = ISB ? bt_expo[set][i] : a_expo[set][PAIRK ? 0 : i];
+                const int bit = ISB ? eb_shift + 8 * (t / 4) : PAIRK ? 16 * i + 8 * (t / 4) : e_shift + 8 * (t / 4);
+                shift = (int)((e >> bit) & 0xFFu) - 133;
             }
             ldf[(u - 1) % 2][0] = ldexpf(cvf[(u - 1) % 2][0], shift);
             ldf[(u - 1) % 2][1] = ldexpf(cvf[(u - 1) % 2][1], shift);
@@ -709,9 +719,9 @@ struct TileKernel {
             // issued after it are younger.  rho >= 2: the barrier ending the last-but-one phase of
             // the next K-step, which leaves the tile almost two K-steps to arrive; younger are the
             // A requests of 2 rho - 1 phases and the next B tile's requests.
-            if constexpr (VEC && BPT > 0 && S::RHO == 1) wait_vm<APT * 2>();
+            if constexpr (VEC && BPT > 0 && S::RHO == 1) wait_vm<A_VMEM>();
             if constexpr (VEC && BPT > 0 && S::RHO >= 2 && s == S::RHO - 2)
-                wait_vm<(2 * S::RHO - 1) * APT * 2 + BPT>();
+                wait_vm<(2 * S::RHO - 1) * A_VMEM + BPT>();
             if constexpr (!(ATB_ABLATE & 64)) switch_barrier();   // the "kernel switch" of the ATB nest
             ATB_STAMP(3);
             phases<ki, s + 1>();
