@@ -236,7 +236,7 @@ atb_status atb_select_tiles(int64_t M, int64_t N, int64_t K, const atb_hw_params
  *                                               prolog (LDS latency, Eq. 4 form) + epilog (barrier)
  *   kstep  = steady + rho * switch              (Eq. 9; workgroups sharing a CU overlap, Eq. 10)
  * mfma_util = mfma / kstep; the chip is power-limited under this kernel, the
- * measured clock follows 1.248 GHz * mfma_util^-0.6 (capped at 2.4), and
+ * measured clock follows 1.339 GHz * mfma_util^-0.617 (capped at 2.4), and
  * pred_flops = flop per K-step * CUs / (kstep / clock).
  * Predicts the full-load throughput of the compiled instances within 15 %
  * from the tile factors and the wave grid alone (tests/golden/mi355x_instances.txt);

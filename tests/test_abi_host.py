@@ -207,8 +207,8 @@ def test_microkernel_model_against_measurements():
         assert m.steady_cycles == pytest.approx(max(m.mfma_cycles, m.valu_cycles, m.lds_cycles, m.vmem_cycles) / 0.85)
         assert m.kstep_cycles == pytest.approx(m.steady_cycles + (tiles[1] // tiles[0]) * m.switch_cycles)
         assert m.mfma_util == pytest.approx(m.mfma_cycles / m.kstep_cycles) and 0 < m.mfma_util < 1
-        if flag == "ok":
-            assert abs(m.pred_flops / 1e12 / tflops - 1) < 0.15, (tiles, m.pred_flops / 1e12, tflops)
+        if flag in ("ok", "loose"):
+            assert abs(m.pred_flops / 1e12 / tflops - 1) < (0.15 if flag == "ok" else 0.25), (tiles, m.pred_flops / 1e12, tflops)
             if busy is not None:
                 assert abs(m.mfma_util - busy) < 0.10, (tiles, m.mfma_util, busy)
     # every large tile is limited by the VALU issue port (decode next to MFMAs), the small ones by the LDS
