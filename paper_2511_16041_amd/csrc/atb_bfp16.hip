@@ -36,19 +36,22 @@ __device__ __forceinline__ void quantize_block(const float (&x)[8], unsigned &E,
     w1 = (int)(b[4] | (b[5] << 8) | (b[6] << 16) | (b[7] << 24));
 }
 
-// One lane per 16 consecutive k of a row (two BFP16 blocks).  Lanes run along K within a row, so the
-// fp32 reads are contiguous; the writes land in the K-panel-major layout: 4 neighbouring lanes fill
-// the 64 mantissa bytes and 8 exponent bytes of one (panel, row).  Chunks beyond K (the tail of the
-// last panel) are written as zero.
+// One lane per 16 consecutive k of a row (two BFP16 blocks).  Lanes are numbered (group of 256 k,
+// row, chunk within the group): a wave covers 4 rows x 256 k, reads 4 runs of 1 KiB of fp32 and writes,
+// per panel of the K-panel-major output, 4 rows x 64 mantissa bytes that are contiguous.  Chunks
+// beyond K (the tail of the last panel) are written as zero.
 __global__ void __launch_bounds__(256) quantize_kernel(const float *__restrict__ A, int64_t lda,
                                                        int8_t *__restrict__ Am, uint8_t *__restrict__ Ae,
                                                        int64_t M, int64_t K, int64_t panels)
 {
-    const int64_t chunks_per_row = panels * (kPanelK / 16);
+    constexpr int CPG = 16;                           // chunks per group of 256 k (4 panels)
+    const int64_t groups = (panels * (kPanelK / 16) + CPG - 1) / CPG;
     const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= M * chunks_per_row) return;
-    const int64_t row = c / chunks_per_row, q = c % chunks_per_row;
-    const int64_t k0 = q * 16;
+    if (c >= groups * M * CPG) return;
+    const int64_t group = c / (M * CPG), row = (c / CPG) % M;
+    const int64_t k0 = (group * CPG + c % CPG) * 16;
+    const int64_t panel = k0 / kPanelK, kin = k0 % kPanelK;
+    if (panel >= panels) return;
     const float *src = A + row * lda + k0;
 
     float x[16];
@@ -69,7 +72,6 @@ __global__ void __launch_bounds__(256) quantize_kernel(const float *__restrict__
     int4 m;
     quantize_block(lo, E0, m.x, m.y);
     quantize_block(hi, E1, m.z, m.w);
-    const int64_t panel = k0 / kPanelK, kin = k0 % kPanelK;
     *reinterpret_cast<int4 *>(Am + (panel * M + row) * kPanelK + kin) = m;
     *reinterpret_cast<unsigned short *>(Ae + (panel * M + row) * (kPanelK / 8) + (kin >> 3)) = (unsigned short)(E0 | (E1 << 8));
 }
@@ -100,7 +102,7 @@ hipError_t launch_quantize(const float *A, int64_t lda, int8_t *Am, uint8_t *Ae,
                            hipStream_t stream)
 {
     const int64_t panels = (K + kPanelK - 1) / kPanelK;
-    const int64_t n = M * panels * (kPanelK / 16);
+    const int64_t n = M * ((panels * (kPanelK / 16) + 15) / 16) * 16;
     if (n == 0) return hipSuccess;
     const int64_t blocks = (n + 255) / 256;
     hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, A, lda, Am, Ae, M, K, panels);
