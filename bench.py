@@ -28,7 +28,7 @@ def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="square8192")
     ap.add_argument("--tiles", default="", help="T_MA,T_MC,T_K,T_N (default: the selector's pick)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the per-instance sweep")
