@@ -225,7 +225,6 @@ struct TileKernel {
     // size down, so the hardware range check keeps masking panels past the last of A and rows >= K of B, and no
     // vector register that a memory instruction has just read is written right after it.
     int a_moff[S::RHO][APTN], a_eoff[S::RHO][APTN], b_off[BPTN];
-    int b_col[BPTN];        // first column of request i's chunk (only used when !VEC)
     const int8_t *am_ptr;              // start of the K-step the next A fetch belongs to
     const uint8_t *ae_ptr;
     const uint16_t *b_ptr;             // start of the K-step the next B fetch belongs to
@@ -348,7 +347,6 @@ struct TileKernel {
             const int slot = slot0 + i * NTS + lane;
             const int row = slot / S::B_CPR, c = (slot % S::B_CPR) ^ ((row & 3) << S::SWZ);
             b_off[i] = (row * p.N + n0 + c * 8) * 2;
-            b_col[i] = n0 + c * 8;
         }
 #pragma unroll
         for (int a = 0; a < S::MTW; ++a)
@@ -444,7 +442,8 @@ struct TileKernel {
     // Request i of the next B tile in fetch order, destined for LDS buffer `buf`.
     // VEC (even N: dword-aligned rows): one 16-byte load per lane straight into LDS (no registers, no ds_write);
     // completion is awaited with wait_b_landed() before the barrier that publishes the tile.
-    // !VEC: element loads into registers, each masked against N; store_b_chunk() writes them later.
+    // !VEC (odd N, rows of B only 2-byte aligned): aligned loads into registers plus a funnel shift;
+    // store_b_chunk() writes them to LDS later.
     template <int i>
     ATB_DEV void load_b_chunk(int buf)
     {
@@ -456,13 +455,15 @@ struct TileKernel {
             (void)buf;   // the host pass only parses this function
 #endif
         } else {
-            const int n = b_col[i];
-            unsigned t[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                t[j] = __builtin_amdgcn_raw_buffer_load_b16(rs.b, (n + j < p.N) ? b_off[i] + 2 * j : kOutOfRange, 0, 0);
-            b_raw[i] = intx4{(int)(t[0] | (t[1] << 16)), (int)(t[2] | (t[3] << 16)),
-                             (int)(t[4] | (t[5] << 16)), (int)(t[6] | (t[7] << 16))};
+            // odd N: a chunk starts at an odd bf16 of its row as often as not.  Fetch the 5 aligned
+            // dwords that contain it and shift by half a dword where needed.
+            const int al = b_off[i] & ~3, sh = (b_off[i] & 2) * 8;
+            const intx4 lo = __builtin_amdgcn_raw_buffer_load_b128(rs.b, al, 0, 0);
+            const int hi = __builtin_amdgcn_raw_buffer_load_b32(rs.b, al + 16, 0, 0);
+            b_raw[i] = intx4{(int)__builtin_amdgcn_alignbit((unsigned)lo.y, (unsigned)lo.x, sh),
+                             (int)__builtin_amdgcn_alignbit((unsigned)lo.z, (unsigned)lo.y, sh),
+                             (int)__builtin_amdgcn_alignbit((unsigned)lo.w, (unsigned)lo.z, sh),
+                             (int)__builtin_amdgcn_alignbit((unsigned)hi, (unsigned)lo.w, sh)};
         }
         if constexpr (i == BPT - 1 && !(ATB_ABLATE & 128)) {
             b_ptr += S::T_K * p.N;
