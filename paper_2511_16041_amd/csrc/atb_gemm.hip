@@ -124,19 +124,8 @@ struct Rsrc {
 };
 
 constexpr int kRsrcFlags = 0x00020000;           // raw buffer, 32-bit data format
-constexpr int kOutOfRange = (int)0x80000000;     // a byte offset no buffer of ours reaches
 
 #define ATB_FENCE() __builtin_amdgcn_sched_barrier(0)
-
-// Developer ablation switches (timing experiments only; results are wrong when non-zero, and since the
-// chip is power-limited and its power depends on the data, a switch that changes the operand values,
-// e.g. by decoding stale registers, overstates what the removed work costs):
-// 2 B fragments read once, 8 no LDS stores of decoded A, 16 no A-fragment reads after the first band,
-// 32 no MFMA, 64 no barrier, 128 global loads never advance (always the first K-step: cache-hot),
-// 256 no A loads, 512 no bf16 B loads, 1024 no exponent loads.
-#ifndef ATB_ABLATE
-#define ATB_ABLATE 0
-#endif
 
 // Per-wave time stamps for kernel tuning (s_memtime at the start of a microkernel, at its end and
 // after the switch barrier, summed per wave of workgroup 0); compiled out of the library: ATB_TRACE
@@ -176,6 +165,9 @@ __device__ unsigned long long atb_trace_acc[16 * 8];
 //                    read into the waves' fragment registers during that band (each fragment
 //                    right after its last use), consumed in K-step kt.
 // The K loop is unrolled by two so that every buffer and register-set index is a constant.
+// The time line does not stop at the end of a tile: when a request stream has asked for the last
+// K-step of its tile it moves on to the first K-step of the workgroup's next tile (open_a, open_b),
+// so K-step 0 of that tile finds its operands staged exactly as any other K-step does.
 //
 // Staging roles.  ROLE 0: every wave stages its share of A and of B.  Workgroups of 8 waves run two
 // waves per SIMD, and the SIMD's arbiter prefers the older one (measured: with equal work the first
@@ -215,7 +207,14 @@ struct TileKernel {
 
     const GemmParams &p;
     Rsrc rs;
-    int tid, lane, wm, wn, m0, n0;
+    int tid, lane, wm, wn;
+    // The workgroup walks its C tiles t_first, t_first + t_stride, ... (see tile_at) as one unbroken
+    // pipeline: the requests for A and for B run ahead of the arithmetic by fixed numbers of K-steps,
+    // across tile boundaries too, so each of the three streams keeps its own position in the walk.
+    int t_stride, kt_steps;            // kt_steps: K-steps per tile, rounded up to a whole loop body
+    int c_t, m0, n0;                   // the tile being accumulated (and stored by the epilogue)
+    int a_t, a_m0, a_steps;            // A requests: tile, the row origin the offsets are based on, K-steps left to request
+    int b_t, b_n0, b_steps;            // B requests: likewise with the column origin
     // LDS byte addresses of this thread's staging writes and fragment reads, per buffer
     char *a_wr[S::AB], *b_wr[2];
     const char *a_rd[S::AB], *b_rd[2][S::NBASE];  // b_rd[buffer][column band mod 4]
@@ -251,8 +250,9 @@ struct TileKernel {
     int shift;
     ATB_TRACE_DECL;
 
-    ATB_DEV TileKernel(const GemmParams &p_, char *lds, int m0_, int n0_) : p(p_), m0(m0_), n0(n0_)
+    ATB_DEV TileKernel(const GemmParams &p_, char *lds, int t_first, int t_stride_) : p(p_), t_stride(t_stride_)
     {
+        kt_steps = (p.K + S::T_K * S::KU - 1) / (S::T_K * S::KU) * S::KU;
         tid = threadIdx.x;
         lane = tid & 63;
         const int wave = tid >> 6;
@@ -290,11 +290,6 @@ struct TileKernel {
                 b_rd[b][e] = b_base + (8 * (blk >> 1) + r) * S::PB + ((chunk ^ (r << S::SWZ)) * 16) + (j & 1) * 8;
             }
         }
-        am_ptr = p.Am;
-        ae_ptr = p.Ae;
-        am_left = p.k_panels * p.M * kPanelK;
-        ae_left = p.k_panels * p.M * (kPanelK / 8);
-        remake_a();
         if constexpr (BBFP) {
             // staging: thread -> (row n = stid / 4 + 64 i, chunk q = stid % 4 ... ) for T_K = 64; in general T_K / 16 chunks per row
             constexpr int CPR = S::T_K / 16;
@@ -307,23 +302,14 @@ struct TileKernel {
                 // B fragment: lane l reads column (row of B^T) l%32 of a band, k = ks*16 + 8*(l/32) .. +7
                 bt_rd[b] = b_base + (wn * S::NTW * 32 + (lane & 31)) * S::PA + (lane >> 5) * 16;
             }
-            bm_ptr = p.Bm;
-            be_ptr = p.Be;
-            bm_left = p.k_panels * p.N * kPanelK;
-            be_left = p.k_panels * p.N * (kPanelK / 8);
-            remake_bt();
             // rows >= N of B^T lie beyond the end of the planes and read as zero
 #pragma unroll
             for (int i = 0; i < BTPT; ++i) {
-                const int grow = n0 + b_row + i * (NTS / CPR);
+                const int grow = b_row + i * (NTS / CPR);
                 const int pnl = (b_q * 16) / kPanelK, kin = (b_q * 16) % kPanelK;
                 bt_moff[i] = (pnl * p.N + grow) * kPanelK + kin;
                 bt_eoff[i] = (pnl * p.N + grow) * (kPanelK / 8) + ((kin / 8) & ~3);
             }
-        } else {
-            b_ptr = p.B;
-            b_left = p.K * p.N * 2;
-            remake_b();
         }
         // Offsets of sub-tile 0 / K-step 0 in the K-panel-major planes: the chunks of a sub-tile follow
         // each other in memory in the order of the staging threads, so a wave's request is one
@@ -334,7 +320,7 @@ struct TileKernel {
         for (int sub = 0; sub < S::RHO; ++sub)
 #pragma unroll
             for (int i = 0; i < APT; ++i) {
-                const int grow = m0 + sub * S::T_MA + a_row + (PAIRK ? 0 : (A_FIRST + i) * (NTS / A_CPR));
+                const int grow = sub * S::T_MA + a_row + (PAIRK ? 0 : (A_FIRST + i) * (NTS / A_CPR));
                 const int cq = PAIRK ? a_q + i : a_q;                  // chunk index within the row
                 const int pnl = (cq * ACE) / kPanelK, kin = (cq * ACE) % kPanelK;
                 a_moff[sub][i] = (pnl * p.M + grow) * kPanelK + kin;
@@ -346,7 +332,7 @@ struct TileKernel {
         for (int i = 0; i < BPT; ++i) {
             const int slot = slot0 + i * NTS + lane;
             const int row = slot / S::B_CPR, c = (slot % S::B_CPR) ^ ((row & 3) << S::SWZ);
-            b_off[i] = (row * p.N + n0 + c * 8) * 2;
+            b_off[i] = (row * p.N + c * 8) * 2;
         }
 #pragma unroll
         for (int a = 0; a < S::MTW; ++a)
@@ -354,6 +340,87 @@ struct TileKernel {
             for (int b = 0; b < S::NTW; ++b)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+        // the offsets above are those of the tile at row 0, column 0; the streams move them to their tiles
+        a_m0 = 0;
+        b_n0 = 0;
+        c_t = t_first;
+        tile_at(c_t, m0, n0);
+        if constexpr (APT > 0) { open_a(t_first); remake_a(); }
+        if constexpr (BTPT > 0) { open_b(t_first); remake_bt(); }
+        if constexpr (BPT > 0) { open_b(t_first); remake_b(); }
+    }
+
+    // Origin of the t-th tile of this workgroup's XCD (false past the end of the walk).  Workgroups
+    // are dealt round-robin to the 8 XCDs (each with its own L2); XCD x owns the contiguous run of
+    // tiles [x * per_xcd, (x + 1) * per_xcd), walked in bands of group_m tile rows so that the
+    // workgroups resident on one XCD share few distinct A row panels and B column panels.
+    ATB_DEV bool tile_at(int t, int &tm0, int &tn0) const
+    {
+        const int total = p.tiles_m * p.tiles_n;
+        const int per_xcd = (total + 7) / 8;
+        const int logical = (int)(blockIdx.x % 8) * per_xcd + t;
+        if (t >= per_xcd || logical >= total) return false;
+        const int band_sz = p.group_m * p.tiles_n;
+        const int band = logical / band_sz, in_band = logical % band_sz;
+        const int rows_here = min(p.group_m, p.tiles_m - band * p.group_m);
+        tm0 = (band * p.group_m + in_band % rows_here) * S::T_MC;
+        tn0 = (in_band / rows_here) * S::T_N;
+        return true;
+    }
+
+    // Point the A requests at the first K-step of tile t of the walk; past the last tile they get
+    // empty buffers, so every request reads zeros without touching memory.  (The caller rebuilds
+    // the descriptors.)
+    ATB_DEV void open_a(int t)
+    {
+        int tm0 = 0, tn0 = 0;
+        a_t = t;
+        am_ptr = p.Am;
+        ae_ptr = p.Ae;
+        if (tile_at(t, tm0, tn0)) {
+            const int d = tm0 - a_m0;
+            a_m0 = tm0;
+#pragma unroll
+            for (int sub = 0; sub < S::RHO; ++sub)
+#pragma unroll
+                for (int i = 0; i < APT; ++i) {
+                    a_moff[sub][i] += d * kPanelK;
+                    a_eoff[sub][i] += d * (kPanelK / 8);
+                }
+            am_left = p.k_panels * p.M * kPanelK;
+            ae_left = p.k_panels * p.M * (kPanelK / 8);
+            a_steps = kt_steps;
+        } else {
+            am_left = ae_left = 0;
+            a_steps = 0x7fffffff;
+        }
+    }
+
+    // The same for the B requests (bf16 B, or B^T in BFP16).
+    ATB_DEV void open_b(int t)
+    {
+        int tm0 = 0, tn0 = 0;
+        b_t = t;
+        const bool live = tile_at(t, tm0, tn0);
+        const int d = live ? tn0 - b_n0 : 0;
+        b_n0 += d;
+        b_steps = live ? kt_steps : 0x7fffffff;
+        if constexpr (BBFP) {
+            bm_ptr = p.Bm;
+            be_ptr = p.Be;
+            bm_left = live ? p.k_panels * p.N * kPanelK : 0;
+            be_left = live ? p.k_panels * p.N * (kPanelK / 8) : 0;
+#pragma unroll
+            for (int i = 0; i < BTPT; ++i) {
+                bt_moff[i] += d * kPanelK;
+                bt_eoff[i] += d * (kPanelK / 8);
+            }
+        } else {
+            b_ptr = p.B;
+            b_left = live ? p.K * p.N * 2 : 0;
+#pragma unroll
+            for (int i = 0; i < BPT; ++i) b_off[i] += d * 2;
+        }
     }
 
     // ---- global -> registers -------------------------------------------------------------
@@ -390,10 +457,14 @@ struct TileKernel {
         bt_mant[set][i] = __builtin_amdgcn_raw_buffer_load_b128(rs.bm, bt_moff[i], 0, 0);
         bt_expo[set][i] = __builtin_amdgcn_raw_buffer_load_b32(rs.be, bt_eoff[i], 0, 0);
         if constexpr (i == BTPT - 1) {
-            bm_ptr += (S::T_K / kPanelK) * p.N * kPanelK;
-            be_ptr += (S::T_K / kPanelK) * p.N * (kPanelK / 8);
-            bm_left = max(bm_left - (S::T_K / kPanelK) * p.N * kPanelK, 0);
-            be_left = max(be_left - (S::T_K / kPanelK) * p.N * (kPanelK / 8), 0);
+            if (--b_steps == 0) {
+                open_b(b_t + t_stride);
+            } else {
+                bm_ptr += (S::T_K / kPanelK) * p.N * kPanelK;
+                be_ptr += (S::T_K / kPanelK) * p.N * (kPanelK / 8);
+                bm_left = max(bm_left - (S::T_K / kPanelK) * p.N * kPanelK, 0);
+                be_left = max(be_left - (S::T_K / kPanelK) * p.N * (kPanelK / 8), 0);
+            }
             remake_bt();
         }
     }
@@ -419,13 +490,17 @@ struct TileKernel {
             a_mant[set][i] = intx4{t.x, t.y, 0, 0};
         }
         // the aligned dword that holds this chunk's exponent byte(s): sub-dword loads are far slower
-        if constexpr (!(ATB_ABLATE & 1024) && (!PAIRK || i == 0))
+        if constexpr (!PAIRK || i == 0)
             a_expo[set][i] = __builtin_amdgcn_raw_buffer_load_b32(rs.ae, a_eoff[sub][i], 0, 0);
-        if constexpr (sub == S::RHO - 1 && i == APT - 1 && !(ATB_ABLATE & 128)) {
-            am_ptr += (S::T_K / kPanelK) * p.M * kPanelK;
-            ae_ptr += (S::T_K / kPanelK) * p.M * (kPanelK / 8);
-            am_left = max(am_left - (S::T_K / kPanelK) * p.M * kPanelK, 0);
-            ae_left = max(ae_left - (S::T_K / kPanelK) * p.M * (kPanelK / 8), 0);
+        if constexpr (sub == S::RHO - 1 && i == APT - 1) {
+            if (--a_steps == 0) {
+                open_a(a_t + t_stride);
+            } else {
+                am_ptr += (S::T_K / kPanelK) * p.M * kPanelK;
+                ae_ptr += (S::T_K / kPanelK) * p.M * (kPanelK / 8);
+                am_left = max(am_left - (S::T_K / kPanelK) * p.M * kPanelK, 0);
+                ae_left = max(ae_left - (S::T_K / kPanelK) * p.M * (kPanelK / 8), 0);
+            }
             remake_a();
         }
     }
@@ -465,9 +540,13 @@ struct TileKernel {
                              (int)__builtin_amdgcn_alignbit((unsigned)lo.w, (unsigned)lo.z, sh),
                              (int)__builtin_amdgcn_alignbit((unsigned)hi, (unsigned)lo.w, sh)};
         }
-        if constexpr (i == BPT - 1 && !(ATB_ABLATE & 128)) {
-            b_ptr += S::T_K * p.N;
-            b_left = max(b_left - S::T_K * p.N * 2, 0);
+        if constexpr (i == BPT - 1) {
+            if (--b_steps == 0) {
+                open_b(b_t + t_stride);
+            } else {
+                b_ptr += S::T_K * p.N;
+                b_left = max(b_left - S::T_K * p.N * 2, 0);
+            }
             remake_b();
         }
     }
@@ -520,10 +599,7 @@ struct TileKernel {
             dec[t % 4] = pk.w;
             if constexpr (t % 4 == 3) {
                 char *dst = dst_base + ((!ISB && PAIRK) ? i * (ACE * 2) : i * ROWS * S::PA) + (t / 4) * 16;
-                if constexpr (ATB_ABLATE & 8)
-                    asm volatile("" ::"v"(dec[0]), "v"(dec[1]), "v"(dec[2]), "v"(dec[3]));
-                else
-                    *reinterpret_cast<intx4 *>(dst) = intx4{(int)dec[0], (int)dec[1], (int)dec[2], (int)dec[3]};
+                *reinterpret_cast<intx4 *>(dst) = intx4{(int)dec[0], (int)dec[1], (int)dec[2], (int)dec[3]};
             }
         }
         if constexpr (u >= 1 && u - 1 < count) {
@@ -556,10 +632,7 @@ struct TileKernel {
     template <int i>
     ATB_DEV void store_b_chunk(char *b_dst)
     {
-        if constexpr (ATB_ABLATE & 8)
-            asm volatile("" ::"v"(b_raw[i]));
-        else
-            *reinterpret_cast<intx4 *>(b_dst + i * (NTS * 16)) = b_raw[i];
+        *reinterpret_cast<intx4 *>(b_dst + i * (NTS * 16)) = b_raw[i];
     }
 
     template <int set>
@@ -641,11 +714,11 @@ struct TileKernel {
         constexpr int n_la = APT, n_lb = (s == 0 ? BPT : 0), n_lt = (s == 0 ? BTPT : 0), n_dt = NPAIR_B / S::RHO;
         constexpr int j1 = n_lb, j2 = j1 + n_lt, j3 = j2 + n_la, j4 = j3 + NSTEP_A, j5 = j4 + NSTEP_B;
         if constexpr (j < j1) {
-            if constexpr (!(ATB_ABLATE & 512)) load_b_chunk<j>(kpar);
+            load_b_chunk<j>(kpar);
         } else if constexpr (j < j2) {
             load_bt_chunk<kpar ^ 1, j - j1>();
         } else if constexpr (j < j3) {
-            if constexpr (!(ATB_ABLATE & 256)) load_a_chunk<g % S::PF, (s + S::PF) % S::RHO, j - j2>();
+            load_a_chunk<g % S::PF, (s + S::PF) % S::RHO, j - j2>();
         } else if constexpr (j < j4) {
             decode_step<false, (g + S::DA) % S::PF, 0, NPAIR, j - j3>(a_wr[(g + S::DA) % S::AB]);
         } else if constexpr (j < j5) {
@@ -679,11 +752,8 @@ struct TileKernel {
             constexpr int nside = n_side<s>();
             constexpr int g = ki * S::RHO + s;
             constexpr int par = (g * S::PER + il) % 2;            // which half of afrag this band uses
-            if constexpr (!(ATB_ABLATE & 32))
-                acc[local][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag[ks][nt], afrag[par][ks],
-                                                                        acc[local][nt], 0, 0, 0);
-            else
-                acc[local][nt][0] += (float)bfrag[ks][nt][0] + (float)afrag[par][ks][0];
+            acc[local][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag[ks][nt], afrag[par][ks],
+                                                                    acc[local][nt], 0, 0, 0);
             ATB_FENCE();
             // the last eighth of the slots carries no side work, so that the LDS stores of the decode
             // have drained when the wave reaches the switch barrier
@@ -691,13 +761,13 @@ struct TileKernel {
             constexpr int j0 = (m * nside) / NS < nside ? (m * nside) / NS : nside;
             constexpr int j1 = ((m + 1) * nside) / NS < nside ? ((m + 1) * nside) / NS : nside;
             side_range<ki, s, j0, j1>();
-            if constexpr (nt == S::NTW - 1 && !(ATB_ABLATE & 16)) {
+            if constexpr (nt == S::NTW - 1) {
                 if constexpr (il + 1 < S::PER)
                     read_a_frag<par ^ 1, il + 1, ks>(a_rd[g % S::AB]);
                 else if constexpr (S::AB == 4)      // first band of the next sub-tile, already complete in LDS
                     read_a_frag<par ^ 1, 0, ks>(a_rd[(g + 1) % S::AB]);
             }
-            if constexpr (last_phase && il + 1 == S::PER && !(ATB_ABLATE & 2)) read_b_frag<ks, nt>(kpar ^ 1);
+            if constexpr (last_phase && il + 1 == S::PER) read_b_frag<ks, nt>(kpar ^ 1);
             ATB_FENCE();
             slots<ki, s, m + 1>();
         }
@@ -723,7 +793,7 @@ struct TileKernel {
             if constexpr (VEC && BPT > 0 && S::RHO == 1) wait_vm<A_VMEM>();
             if constexpr (VEC && BPT > 0 && S::RHO >= 2 && s == S::RHO - 2)
                 wait_vm<(2 * S::RHO - 1) * A_VMEM + BPT>();
-            if constexpr (!(ATB_ABLATE & 64)) switch_barrier();   // the "kernel switch" of the ATB nest
+            switch_barrier();   // the "kernel switch" of the ATB nest
             ATB_STAMP(3);
             phases<ki, s + 1>();
         }
@@ -772,16 +842,26 @@ struct TileKernel {
         switch_barrier();
         if constexpr (S::AB == 4) read_first_band<0>(a_rd[0]);
 
-        // the number of K-steps is rounded up to a whole loop body: the extra steps multiply by
-        // B rows >= K, which read as zero
-        const int KT = (p.K + S::T_K - 1) / S::T_K;
+        // The number of K-steps is rounded up to a whole loop body: the extra steps multiply by B rows
+        // >= K, which read as zero.  The last K-steps of a tile already request, decode and stage the
+        // first operands of the workgroup's next tile (the request streams have moved on to it), so the
+        // next tile needs no prologue: the epilogue is all that separates two tiles' arithmetic.
         ATB_STAMP(0);
-        for (int kt = 0; kt < KT; kt += S::KU) ksteps<0>();
+        for (;;) {
+            for (int kt = 0; kt < kt_steps; kt += S::KU) ksteps<0>();
+            if constexpr (CBFP) store_c_bfp(); else store_c();
+            c_t += t_stride;
+            if (!tile_at(c_t, m0, n0)) break;
+#pragma unroll
+            for (int a = 0; a < S::MTW; ++a)
+#pragma unroll
+                for (int b = 0; b < S::NTW; ++b)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+        }
         ATB_TRACE_FLUSH();
-        // the requests for the two K-steps past the end (they read zeros) must not be in flight when
-        // the next tile of this workgroup re-uses the registers and LDS buffers they target
+        // the requests past the end of the walk (they read zeros) target registers and LDS of this wave
         wait_vm<0>();
-        if constexpr (CBFP) store_c_bfp(); else store_c();
     }
 
     // epilogue: fp32 -> bf16 (round to nearest even) and store, once per tile.  Lane l of band
@@ -862,30 +942,19 @@ struct TileKernel {
     }
 };
 
-// Workgroup -> C tiles.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2); XCD x
-// owns the contiguous run of tiles [x * per_xcd, (x + 1) * per_xcd), walked in bands of group_m tile
-// rows so that the workgroups resident on one XCD share few distinct A row panels and B column panels.
-// For the large tiles the grid is persistent: it holds only as many workgroups as fit on the chip at
-// once, and workgroup b serves tiles b / 8, b / 8 + gridDim.x / 8, ... of its XCD's run.  The stores of one tile's epilogue
-// then drain while the next tile's first requests are already in flight, and no tile waits for a
-// workgroup launch.
+// Workgroup -> C tiles (TileKernel::tile_at has the mapping).  For the large tiles the grid is
+// persistent: it holds only as many workgroups as fit on the chip at once, and workgroup b serves
+// tiles b / 8, b / 8 + gridDim.x / 8, ... of its XCD's run as one pipeline, so no tile waits for a
+// workgroup launch or for its first operands.
 template <class S, bool VEC, int ROLE, bool BBFP, bool CBFP>
 __device__ __forceinline__ void tile_loop(const GemmParams &p, char *lds)
 {
     const int total = p.tiles_m * p.tiles_n;
     const int per_xcd = (total + 7) / 8;
-    const int stride = (int)gridDim.x / 8;
-    const int band_sz = p.group_m * p.tiles_n;
-    for (int t = (int)blockIdx.x / 8; t < per_xcd; t += stride) {
-        const int logical = (int)(blockIdx.x % 8) * per_xcd + t;
-        if (logical >= total) break;
-        const int band = logical / band_sz, in_band = logical % band_sz;
-        const int rows_here = min(p.group_m, p.tiles_m - band * p.group_m);
-        const int tm = band * p.group_m + in_band % rows_here;
-        const int tn = in_band / rows_here;
-        TileKernel<S, VEC, ROLE, BBFP, CBFP> tile(p, lds, tm * S::T_MC, tn * S::T_N);
-        tile.run();
-    }
+    const int first = (int)blockIdx.x / 8;
+    if (first >= per_xcd || (int)(blockIdx.x % 8) * per_xcd + first >= total) return;   // the whole workgroup leaves
+    TileKernel<S, VEC, ROLE, BBFP, CBFP> tile(p, lds, first, (int)gridDim.x / 8);
+    tile.run();
 }
 
 template <class S, bool VEC, bool BBFP = false, bool CBFP = false>

@@ -164,3 +164,30 @@ def test_bfp16_output_feeds_the_next_gemm(tiles):
     assert np.array_equal(gm, c1m) and np.array_equal(ge, c1e) and not pad.any()
     err = np.abs(oracle.bf16_to_double(bf16_tensor_bits(C2_dev)) - oracle.bf16_to_double(C2_ref))
     assert not np.isnan(err).any() and not (err > oracle.tolerance(T2)).any()
+
+
+@pytest.mark.parametrize("tiles", [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256)])
+@pytest.mark.parametrize("fmt", COMBOS)
+@pytest.mark.parametrize("shape", [(4300, 4400, 8), (4600, 4360, 136)])
+def test_formats_across_tile_boundaries(tiles, fmt, shape):
+    """More 256 x 256 tiles than resident workgroups: the BFP16 B stream (three K-steps ahead) and the
+    BFP16 epilogue run across the boundaries between a workgroup's tiles."""
+    b_format, c_format = fmt
+    M, N, K = shape
+    print(f"formats chain {shape} tiles={tiles} B={b_format} C={c_format}", flush=True)
+    A, Bt = _inputs(M, N, K, seed=5, exact=False)
+    mant, expo, bmant, bexpo, Bq_bits = _reference(A, Bt)
+    C_ref, T, S, _ = oracle.gemm(mant, expo, Bq_bits, want_sum=True)
+    B_arg = (bmant, bexpo) if b_format == "bfp16" else Bq_bits
+    got = _run(mant, expo, B_arg, M, N, K, tiles, b_format, c_format)
+    tol = oracle.tolerance(T)
+    if c_format == "bfp16":
+        cm, ce, pad = got
+        step = np.repeat(np.ldexp(1.0, ce.astype(np.int64) - 134), 8, axis=1)
+        err = np.abs(oracle.decode(cm, ce) - S)
+        assert not (err > tol + step).any(), f"worst {np.max(err / (tol + step)):.3g}"
+        assert not pad.any()
+    else:
+        err = np.abs(oracle.bf16_to_double(got) - oracle.bf16_to_double(C_ref))
+        assert not np.isnan(err).any()
+        assert not (err > tol).any(), f"worst ratio {np.max(err / tol):.3g}"

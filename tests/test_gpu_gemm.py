@@ -169,3 +169,18 @@ def test_more_tiles_than_resident_workgroups(tiles):
     mant, expo = oracle.quantize(A)
     C_ref, T, _ = oracle.gemm(mant, expo, Bb)
     _check(_run(mant, expo, Bb, tiles), C_ref, T, f"persistent {tiles}")
+
+
+@pytest.mark.parametrize("tiles", BIG + WIDE_K)
+@pytest.mark.parametrize("shape", [(4300, 4400, 8), (4300, 4400, 128), (5900, 5700, 72), (4353, 4609, 200)])
+def test_tile_chain_lengths(tiles, shape):
+    """A workgroup of the persistent grid runs its tiles as one pipeline: the requests for a tile's first
+    operands are issued during the previous tile's last K-steps.  K = 8 and 128 make a tile two K-steps
+    long, so the request streams cross a tile boundary inside the prologue and again in every loop body;
+    23 x 23 tiles give most workgroups two tiles and some three; the edge tiles are one row or column wide."""
+    M, N, K = shape
+    print(f"gemm chain {shape} {tiles}", flush=True)
+    A, Bb = workloads.make_inputs(workloads.CONFIGS["ragged"], M=M, N=N, K=K)
+    mant, expo = oracle.quantize(A)
+    C_ref, T, _ = oracle.gemm(mant, expo, Bb)
+    _check(_run(mant, expo, Bb, tiles), C_ref, T, f"chain {shape} {tiles}")
