@@ -112,6 +112,91 @@ double run(float *out, int iters)     // nanoseconds per iteration
     return ms * 1e6 / iters;
 }
 
+__device__ __forceinline__ unsigned rnd_bf16x2(unsigned &r) { r = r * 1664525u + 1013904223u; return (r & 0x807F807Fu) | 0x3C003C00u | ((r >> 3) & 0x03800380u); }
+
+// The GEMM kernel's on-CU instruction mix on pseudo-random operands, built up step by step, with no global
+// memory traffic and no barriers: what the power limit leaves of the matrix pipes' throughput once the
+// fragment reads, the decode and the staging stores run next to them.  F is a set of flags:
+// 1: the MFMA operands rotate over 4 register sets (they change from one MFMA to the next, as in the GEMM);
+// 2: the operands come from LDS, one b128 A fragment and one transposing b64 B half-fragment per 2 MFMAs
+//    (the GEMM's 2 x 4 wave grid: 16 + 16 reads per 32 MFMAs);
+// 4: waves 0-3 decode one BFP16 pair per MFMA (half a pair per MFMA over the SIMD's two waves);
+// 8: waves 0-3 store 16 decoded bytes per lane to LDS every 8 MFMAs.
+template <int F>
+__global__ void __launch_bounds__(kThreads) mix_kernel(float *out, int iters, int seed)
+{
+    __shared__ __attribute__((aligned(16))) char lds[kLds];
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    unsigned r = t * 2654435761u + 12345u + blockIdx.x;
+    for (int i = t; i < kLds / 4; i += kThreads) reinterpret_cast<unsigned *>(lds)[i] = rnd_bf16x2(r);
+    __syncthreads();
+    bf16x8 a[4], b[4];
+    for (int s = 0; s < 4; ++s) {
+        union { unsigned u[4]; bf16x8 v; } ua, ub;
+        for (int e = 0; e < 4; ++e) { ua.u[e] = rnd_bf16x2(r); ub.u[e] = rnd_bf16x2(r); }
+        a[s] = ua.v; b[s] = ub.v;
+    }
+    floatx16 acc[8];
+    for (int i = 0; i < 8; ++i) for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    int w0 = seed + t, sh = seed & 3;
+    unsigned dsum = 0;
+    const char *frag = lds + (wave & 3) * 4608 + (lane & 31) * 144 + (lane >> 5) * 16;
+    const int blk = lane >> 4, j = lane & 15, rr = j >> 2;
+    const char *tr = lds + 24576 + (8 * (blk >> 1) + rr) * 512 + (((4 * (wave & 3) + 2 * (blk & 1) + ((j & 3) >> 1)) ^ (rr << 2)) * 16) + (j & 1) * 8;
+    char *wr = lds + 36864 + (t >> 2) * 144 + (t & 3) * 32;
+    typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int s = (F & 1) ? (i & 3) : 0;
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[(F & 1) ? ((i >> 1) & 3) : 0], a[s], acc[i], 0, 0, 0);
+            FENCE();
+            if (F & 2) {
+                if ((i & 1) == 0)      // one A fragment per 2 MFMAs, replacing the set used two MFMAs ago
+                    a[(i + 2) & 3] = *reinterpret_cast<const bf16x8 *>(frag + ((it + i) & 3) * 32);
+                else {                  // one B half-fragment (tr_b64) per 2 MFMAs
+                    union { shortx4 s[2]; bf16x8 v; } u; u.v = b[((i >> 1) + 2) & 3];
+                    u.s[(i >> 1) & 1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(tr + ((it + i) & 1) * 2048 + ((i >> 1) & 1) * 256));
+                    b[((i >> 1) + 2) & 3] = u.v;
+                }
+            }
+            if ((F & 4) && wave < 4) {
+                const float f0 = ldexpf(byte_to_float(w0, (2 * i) & 3), sh), f1 = ldexpf(byte_to_float(w0, (2 * i + 1) & 3), sh);
+                union { bf16x2 p; unsigned u; } pk;
+                pk.p = bf16x2{(__bf16)f0, (__bf16)f1};
+                dsum ^= pk.u;
+                w0 += 0x01010101;
+            }
+            if ((F & 8) && wave < 4 && i == 7) {
+                *reinterpret_cast<intx4 *>(wr + (it & 1) * 16) = intx4{(int)dsum, w0, (int)dsum ^ w0, it};
+            }
+            FENCE();
+        }
+    }
+    float s = (float)dsum;
+    for (int i = 0; i < 8; ++i) for (int q = 0; q < 16; ++q) s += acc[i][q];
+    __syncthreads();
+    s += reinterpret_cast<const float *>(lds)[t];
+    out[blockIdx.x * kThreads + t] = s;
+}
+
+template <int F>
+void run_mix(float *out, int iters, const char *what)
+{
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
+    hipLaunchKernelGGL((mix_kernel<F>), dim3(kBlocks), dim3(kThreads), 0, 0, out, 2000, 1);
+    CK(hipDeviceSynchronize());
+    CK(hipEventRecord(e0));
+    hipLaunchKernelGGL((mix_kernel<F>), dim3(kBlocks), dim3(kThreads), 0, 0, out, iters, 1);
+    CK(hipEventRecord(e1));
+    CK(hipEventSynchronize(e1));
+    float ms;
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    const double x = ms * 1e6 / iters / 16.0;
+    printf("mix_kernel<%2d>   %-62s %6.2f ns per MFMA per SIMD = %.0f TFLOP/s\n", F, what, x, 32768.0 * 1024 / x / 1e3);
+}
+
 int main()
 {
     float *out;
@@ -132,5 +217,11 @@ int main()
     x = run<0, 0>(out, 1000000) / 16.0; printf("cost_kernel<0,0>  MFMA only, constant operands, 1e6 iterations: %6.2f ns per MFMA per SIMD = %.0f TFLOP/s\n", x, 32768.0 * 1024 / x / 1e3);
     x = run<4, 0>(out, 1000000) / 16.0; printf("cost_kernel<4,0>  MFMA only, random operands,   1e6 iterations: %6.2f ns per MFMA per SIMD = %.0f TFLOP/s\n", x, 32768.0 * 1024 / x / 1e3);
     x = run<4, 1>(out, 1000000) / 16.0; printf("cost_kernel<4,1>  random operands + 1 decode pair per MFMA:     %6.2f ns per MFMA per SIMD = %.0f TFLOP/s\n", x, 32768.0 * 1024 / x / 1e3);
+    // the GEMM's instruction mix on random operands, 7e5 iterations each (0.2 - 0.3 s)
+    run_mix<1>(out, 700000, "MFMA only, operands rotate over 4 register sets");
+    run_mix<3>(out, 700000, "+ operands from LDS (0.5 b128 + 0.5 tr_b64 per MFMA)");
+    run_mix<7>(out, 700000, "+ half a BFP16 decode pair per MFMA (waves 0-3)");
+    run_mix<15>(out, 700000, "+ LDS stores of the decoded A (waves 0-3)");
+    run_mix<5>(out, 700000, "register operands + the decode, no LDS");
     return 0;
 }
