@@ -6,7 +6,7 @@
 //       for normal x; fp32 subnormals and zeros contribute 0),
 //   m = clamp(round_to_nearest_even(x * 2^(133 - E)), -127, 127),
 //   value = m * 2^(E - 133).
-// Both kernels are HBM-bound streaming kernels: 16 elements per lane, 16-byte accesses.  The BFP16
+// Both kernels are HBM-bound streaming kernels.  The BFP16
 // buffer is K-panel-major (see include/atb.h): [panel of 64 k][row][64] mantissas, [panel][row][8] exponents.
 #include "atb_internal.h"
 
@@ -17,63 +17,50 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 __device__ __forceinline__ unsigned exp_field(float x) { return (__float_as_uint(x) >> 23) & 0xFFu; }
 
-// Quantise 8 values that share exponent E; returns the mantissas packed little-endian in two words.
-__device__ __forceinline__ void quantize_block(const float (&x)[8], unsigned &E, int &w0, int &w1)
-{
-    unsigned e = 0;
-#pragma unroll
-    for (int t = 0; t < 8; ++t) e = max(e, exp_field(x[t]));
-    E = e;
-    const int shift = 133 - (int)e;
-    unsigned b[8];
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-        float r = rintf(ldexpf(x[t], shift));           // exact power-of-two scaling, then RNE
-        r = fminf(fmaxf(r, -127.0f), 127.0f);
-        b[t] = (unsigned)((int)r) & 0xFFu;
-    }
-    w0 = (int)(b[0] | (b[1] << 8) | (b[2] << 16) | (b[3] << 24));
-    w1 = (int)(b[4] | (b[5] << 8) | (b[6] << 16) | (b[7] << 24));
-}
-
-// One lane per 16 consecutive k of a row (two BFP16 blocks).  Lanes are numbered (group of 256 k,
-// row, chunk within the group): a wave covers 4 rows x 256 k, reads 4 runs of 1 KiB of fp32 and writes,
-// per panel of the K-panel-major output, 4 rows x 64 mantissa bytes that are contiguous.  Chunks
-// beyond K (the tail of the last panel) are written as zero.
+// Quantiser.  A wave covers 16 rows x 128 k (two panels of the K-panel-major output); the 4 waves of a
+// workgroup sit side by side along k.  In step v lanes 0-31 take row 2v and lanes 32-63 row 2v + 1, four
+// consecutive k each, so a load instruction reads two contiguous runs of 512 B and the mantissa store of the
+// same step writes, per panel, the 2 x 64 B of the row pair, which are one 128-byte line of the output.  A
+// BFP16 block is the 8 values of two neighbouring lanes, which exchange their exponent maxima.  The 16 x 16
+// exponent bytes of the wave are collected in LDS and leave as two contiguous runs of 128 B.  Chunks beyond K
+// (the tail of the last panel) are written as zero.
 __global__ void __launch_bounds__(256) quantize_kernel(const float *__restrict__ A, int64_t lda,
                                                        int8_t *__restrict__ Am, uint8_t *__restrict__ Ae,
-                                                       int64_t M, int64_t K, int64_t panels)
+                                                       int64_t M, int64_t K, int64_t panels, int64_t kblocks)
 {
-    constexpr int CPG = 16;                           // chunks per group of 256 k (4 panels)
-    const int64_t groups = (panels * (kPanelK / 16) + CPG - 1) / CPG;
-    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (c >= groups * M * CPG) return;
-    const int64_t group = c / (M * CPG), row = (c / CPG) % M;
-    const int64_t k0 = (group * CPG + c % CPG) * 16;
-    const int64_t panel = k0 / kPanelK, kin = k0 % kPanelK;
-    if (panel >= panels) return;
-    const float *src = A + row * lda + k0;
-
-    float x[16];
-    if (k0 + 16 <= K) {
+    __shared__ __attribute__((aligned(8))) uint8_t exps[4][2][16][8];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, half = lane >> 5, q = lane & 31;
+    const int64_t r0 = ((int64_t)blockIdx.x / kblocks) * 16;
+    const int64_t kg = ((int64_t)blockIdx.x % kblocks) * 4 + wave;       // group of 128 k
+    const int64_t k = kg * 128 + 4 * q;
+    const int64_t panel = kg * 2 + (q >> 4);
+    const int kin = 4 * (q & 15);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            float4 f = *reinterpret_cast<const float4 *>(src + 4 * v);
-            x[4 * v] = f.x; x[4 * v + 1] = f.y; x[4 * v + 2] = f.z; x[4 * v + 3] = f.w;
+    for (int v = 0; v < 8; ++v) {
+        const int64_t row = r0 + 2 * v + half;
+        float4 f = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (row < M && k < K) f = *reinterpret_cast<const float4 *>(A + row * lda + k);     // K % 8 == 0: k < K implies k + 4 <= K
+        unsigned e = max(max(exp_field(f.x), exp_field(f.y)), max(exp_field(f.z), exp_field(f.w)));
+        e = max(e, (unsigned)__shfl_xor((int)e, 1));
+        const int shift = 133 - (int)e;
+        const float x[4] = {f.x, f.y, f.z, f.w};
+        unsigned w = 0;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            float r = rintf(ldexpf(x[t], shift));           // exact power-of-two scaling, then RNE
+            r = fminf(fmaxf(r, -127.0f), 127.0f);
+            w |= ((unsigned)((int)r) & 0xFFu) << (8 * t);
         }
-    } else {
-#pragma unroll
-        for (int t = 0; t < 16; ++t) x[t] = (k0 + t < K) ? src[t] : 0.0f;
+        if (row < M && panel < panels) *reinterpret_cast<unsigned *>(Am + (panel * M + row) * kPanelK + kin) = w;
+        if ((q & 1) == 0) exps[wave][q >> 4][2 * v + half][(q & 15) >> 1] = (uint8_t)e;
     }
-    float lo[8], hi[8];
-#pragma unroll
-    for (int t = 0; t < 8; ++t) { lo[t] = x[t]; hi[t] = x[8 + t]; }
-    unsigned E0, E1;
-    int4 m;
-    quantize_block(lo, E0, m.x, m.y);
-    quantize_block(hi, E1, m.z, m.w);
-    *reinterpret_cast<int4 *>(Am + (panel * M + row) * kPanelK + kin) = m;
-    *reinterpret_cast<unsigned short *>(Ae + (panel * M + row) * (kPanelK / 8) + (kin >> 3)) = (unsigned short)(E0 | (E1 << 8));
+    __syncthreads();
+    if (lane < 32) {
+        const int pl = lane >> 4, rl = lane & 15;
+        const int64_t row = r0 + rl, pn = kg * 2 + pl;
+        if (row < M && pn < panels)
+            *reinterpret_cast<uint2 *>(Ae + (pn * M + row) * (kPanelK / 8)) = *reinterpret_cast<const uint2 *>(&exps[wave][pl][rl][0]);
+    }
 }
 
 __global__ void __launch_bounds__(256) decode_kernel(const int8_t *__restrict__ Am, const uint8_t *__restrict__ Ae,
@@ -102,10 +89,10 @@ hipError_t launch_quantize(const float *A, int64_t lda, int8_t *Am, uint8_t *Ae,
                            hipStream_t stream)
 {
     const int64_t panels = (K + kPanelK - 1) / kPanelK;
-    const int64_t n = M * ((panels * (kPanelK / 16) + 15) / 16) * 16;
-    if (n == 0) return hipSuccess;
-    const int64_t blocks = (n + 255) / 256;
-    hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, A, lda, Am, Ae, M, K, panels);
+    if (M == 0 || panels == 0) return hipSuccess;
+    const int64_t kblocks = (panels + 7) / 8;            // a workgroup covers 16 rows x 512 k = 8 panels
+    const int64_t blocks = ((M + 15) / 16) * kblocks;
+    hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, A, lda, Am, Ae, M, K, panels, kblocks);
     return hipGetLastError();
 }
 
