@@ -220,15 +220,18 @@ def select_tiles(M: int, N: int, K: int, hw: Optional[HwParams] = None) -> List[
 
 # ------------------------------------------------------------------ device calls
 
-def bfp16_quantize(A_f32, stream=None):
-    """A_f32: CUDA fp32 tensor [M][K] (row stride a multiple of 4) -> uint8 tensor holding the A_bfp buffer."""
+def bfp16_quantize(A_f32, stream=None, out=None):
+    """A_f32: CUDA fp32 tensor [M][K] (row stride a multiple of 4) -> uint8 tensor holding the A_bfp buffer
+    (`out`, if given: a CUDA uint8 tensor of bfp16_bytes(M, K) elements, else a new one)."""
     import torch
     assert A_f32.is_cuda and A_f32.dtype == torch.float32 and A_f32.dim() == 2 and A_f32.stride(1) == 1
     M, K = A_f32.shape
     nbytes = bfp16_bytes(M, K)
     if nbytes == 0:
         raise AtbError(1, "atb_bfp16_bytes")
-    out = torch.empty(nbytes, dtype=torch.uint8, device=A_f32.device)
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=A_f32.device)
+    assert out.is_cuda and out.dtype == torch.uint8 and out.is_contiguous() and out.numel() == nbytes
     _check(lib().atb_bfp16_quantize(ctypes.c_void_p(A_f32.data_ptr()), A_f32.stride(0),
                                     ctypes.c_void_p(out.data_ptr()), M, K, _stream_ptr(stream)), "atb_bfp16_quantize")
     return out
