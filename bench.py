@@ -109,6 +109,22 @@ def time_plan(plan, A_bfp, B, C, steps, warmup):
     return wall, ev0.elapsed_time(ev1) / steps
 
 
+def time_per_launch(plan, sets, launches):
+    """`launches` launches, each between its own pair of events on the launch stream (no host sync in
+    between), cycling through the operand sets `sets` = [(A_bfp, B, C), ...].  Returns the list of ms."""
+    import torch
+    for i in range(min(5, launches)):
+        plan.run(*sets[i % len(sets)])
+    torch.cuda.synchronize()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(launches + 1)]
+    evs[0].record()
+    for i in range(launches):
+        plan.run(*sets[i % len(sets)])
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    return [evs[i].elapsed_time(evs[i + 1]) for i in range(launches)]
+
+
 def main():
     args = parse_args()
     if args.copy_probe:
@@ -160,6 +176,18 @@ def main():
     ms_per_step = wall / args.steps * 1e3
     tflops = flop / (wall / args.steps) / 1e12
     kernel_tflops = flop / (kernel_ms * 1e-3) / 1e12
+    # per-launch spread with resident operands, and one figure with cold caches: the operand sets rotate, and
+    # the bytes touched between two uses of a set exceed the 256 MiB memory-side cache (and the 32 MiB of L2)
+    per = sorted(time_per_launch(plan, [(A_bfp, B, C)], 50))
+    set_bytes = A_bfp.numel() + 2 * B.numel() + 2 * C.numel()
+    n_sets = int(min(64, max(2, -(-(384 << 20) // set_bytes) + 1)))
+    sets = [(A_bfp, B, C)] + [(A_bfp.clone(), B.clone(), torch.empty_like(C)) for _ in range(n_sets - 1)]
+    cold = sorted(time_per_launch(plan, sets, max(12, 3 * n_sets)))
+    del sets
+    detail = {"launches": len(per), "median_ms": round(per[len(per) // 2], 4), "min_ms": round(per[0], 4),
+              "cold_cache": {"operand_sets": n_sets, "bytes_per_set": int(set_bytes), "launches": len(cold),
+                             "median_ms": round(cold[len(cold) // 2], 4),
+                             "tflops": round(flop / (cold[len(cold) // 2] * 1e-3) / 1e12, 1)}}
     plan.close()
 
     sweep = []
@@ -204,6 +232,7 @@ def main():
                      "kernel": "atb_gemm_kernel", "kernel_ms": round(kernel_ms, 4),
                      "algorithmic_flop_per_launch": flop},
     }
+    out["per_launch"] = detail
     out["quantizer"] = {"kernel": "quantize_kernel", "ms": round(quant_ms, 4), "bound": "hbm",
                         "achieved": round(5.125 * M * K / (quant_ms * 1e-3) / 1e9, 1), "peak": 8000.0, "unit": "GB/s",
                         "frac": round(5.125 * M * K / (quant_ms * 1e-3) / 8e12, 4),
