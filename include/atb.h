@@ -75,6 +75,11 @@ typedef struct atb_gemm atb_gemm; /* opaque plan, HOST memory */
  * T_MC % T_MA == 0, and the factors must name a compiled instance (see
  * atb_instance_count / atb_instance_get).  M and N need not be multiples of
  * the tile (edge tiles are masked); K need not be a multiple of T_K.
+ * Size limits (32-bit element offsets inside the kernel; ATB_ERR_INVALID_ARG
+ * beyond them): M, N <= 2^23, K <= 2^24, every operand below 2^31 elements
+ * (M * round_up(K, 64), K * N, M * N; also N * round_up(K, 64) and
+ * M * round_up(N, 64) for the BFP16 forms of B and C), and
+ * 2 * N * (T_K + 1) < 2^31.
  * On success *out is a new plan, else *out = NULL. */
 atb_status atb_gemm_create(atb_gemm **out, int64_t M, int64_t N, int64_t K,
                            int T_MA, int T_MC, int T_K, int T_N);

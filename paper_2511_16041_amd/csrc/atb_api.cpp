@@ -125,6 +125,8 @@ extern "C" atb_status atb_gemm_create_fmt(atb_gemm **out, int64_t M, int64_t N, 
         return ATB_ERR_INVALID_ARG;
     if (T_MA < 1 || T_MC < 1 || T_K < 1 || T_N < 1) return ATB_ERR_INVALID_ARG;
     if (T_MC % T_MA != 0) return ATB_ERR_BAD_TILE;
+    // byte offsets of a B tile's requests relative to its first row are 32-bit
+    if (N * ((int64_t)T_K + 1) * 2 >= ((int64_t)1 << 31)) return ATB_ERR_INVALID_ARG;
     // budgets of one CU: A (double-buffered, bf16) and B (double-buffered, bf16) in 160 KiB of LDS,
     // the fp32 C tile in 4 waves x 256 accumulator registers
     if ((int64_t)4 * T_MC * T_N > 256 * 1024) return ATB_ERR_REG_BUDGET;

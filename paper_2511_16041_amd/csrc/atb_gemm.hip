@@ -227,7 +227,8 @@ struct TileKernel {
     const int8_t *am_ptr;              // start of the K-step the next A fetch belongs to
     const uint8_t *ae_ptr;
     const uint16_t *b_ptr;             // start of the K-step the next B fetch belongs to
-    int am_left, ae_left, b_left;      // bytes from those starts to the end of the planes
+    int am_left, ae_left;              // bytes from those starts to the end of the planes
+    int64_t b_left;                    // likewise for B, which may be larger than 2^31 bytes
     int e_shift;                       // bit position of this thread's exponent byte(s) in the loaded dword
     // B in BFP16: this thread's chunks of the B^T tile (row n, 16 mantissas), like the A members
     char *bt_wr[2];
@@ -417,7 +418,7 @@ struct TileKernel {
             }
         } else {
             b_ptr = p.B;
-            b_left = live ? p.K * p.N * 2 : 0;
+            b_left = live ? (int64_t)p.K * p.N * 2 : 0;
 #pragma unroll
             for (int i = 0; i < BPT; ++i) b_off[i] += d * 2;
         }
@@ -441,7 +442,8 @@ struct TileKernel {
         rs.ae = make_rsrc(ae_ptr, ae_left);
     }
 
-    ATB_DEV void remake_b() { rs.b = make_rsrc(b_ptr, b_left); }
+    // a K-step's offsets stay below 2^31, so a longer remainder may be cut off there
+    ATB_DEV void remake_b() { rs.b = make_rsrc(b_ptr, (int)min(b_left, (int64_t)0x7fffffff)); }
 
     ATB_DEV void remake_bt()
     {
@@ -545,7 +547,7 @@ struct TileKernel {
                 open_b(b_t + t_stride);
             } else {
                 b_ptr += S::T_K * p.N;
-                b_left = max(b_left - S::T_K * p.N * 2, 0);
+                b_left = max(b_left - (int64_t)S::T_K * p.N * 2, (int64_t)0);
             }
             remake_b();
         }

@@ -235,3 +235,21 @@ def test_host_packers_agree():
         for unpack in (unpack_a_bfp, atb.bfp16_unpack_host):
             m2, e2, pad = unpack(a, M, K)
             assert np.array_equal(m2, mant) and np.array_equal(e2, expo) and not pad.any()
+
+
+def test_create_rejects_sizes_beyond_32_bit_offsets():
+    """The documented size limits: every operand below 2^31 elements, a B tile's byte offsets below 2^31."""
+    import ctypes
+    L = atb.lib()
+    h = ctypes.c_void_p()
+    def create(M, N, K, tiles=(128, 256, 64, 256)):
+        return L.atb_gemm_create(ctypes.byref(h), M, N, K, *tiles)
+    assert create(256, 32768, 32768) == 0                    # K * N = 2^30 elements: B is 2 GiB, allowed
+    L.atb_gemm_destroy(h)
+    assert create(256, 65536, 32768) == 1                    # K * N = 2^31
+    assert create(65536, 32768, 64) == 1                     # M * N = 2^31
+    assert create(32768, 256, 65536) == 1                    # M * K = 2^31
+    assert create(64, (1 << 23) + 256, 64) == 1              # N > 2^23
+    assert create(64, 1 << 23, 64, (32, 256, 128, 256)) == 1  # 2 N (T_K + 1) >= 2^31 with T_K = 128
+    assert create(64, 1 << 23, 64, (128, 256, 64, 256)) == 0
+    L.atb_gemm_destroy(h)

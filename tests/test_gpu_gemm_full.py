@@ -96,3 +96,32 @@ def test_full_size_all_bfp16_sampled_rows(name, tiles):
     err = np.abs(val - S)
     lim = oracle.tolerance(T) + step
     assert not (err > lim).any(), f"worst ratio {np.max(err / lim):.3g}"
+
+
+@pytest.mark.parametrize("tiles", [(128, 256, 64, 256), (64, 128, 64, 128)])
+def test_b_of_two_gib(tiles):
+    """K * N = 2^30: B spans 2^31 bytes, more than a 32-bit signed byte count.  Small-integer inputs make every
+    fp32 sum exact, so sampled rows of C must equal the oracle's bit for bit: a B row read from the wrong place,
+    or as zero, cannot hide inside a tolerance."""
+    import torch
+    M, N, K = 300, 32768, 32768
+    print(f"B of 2 GiB {tiles}: generating", flush=True)
+    rng = np.random.default_rng(21)
+    A, _ = workloads.small_integer_inputs(M, 8, K, seed=21)
+    lut = workloads.fp32_to_bf16_bits(np.arange(-4, 5, dtype=np.float32))
+    # every row of B is different; along N the pattern repeats every 2048 columns (which keeps the generation short)
+    Bb = np.tile(lut[rng.integers(0, 9, size=(K, 2048), dtype=np.uint8)], (1, N // 2048))
+    mant, expo = oracle.quantize(A)
+    rows = np.array([0, 1, 127, 128, 255, 256, 299], dtype=np.int64)
+    print(f"B of 2 GiB {tiles}: oracle on {rows.size} rows", flush=True)
+    C_ref, _, _ = oracle.gemm(mant, expo, Bb, rows=rows)
+    A_bfp = atb.bfp16_quantize(torch.from_numpy(A).cuda())
+    B_dev = bits_to_bf16_tensor(Bb, "cuda")
+    del Bb
+    C = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    g = atb.Gemm(M, N, K, *tiles)
+    g.run(A_bfp, B_dev, C)
+    torch.cuda.synchronize()
+    g.close()
+    got = bf16_tensor_bits(C[torch.from_numpy(rows).cuda()])
+    assert np.array_equal(got, C_ref)
