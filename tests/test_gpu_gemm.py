@@ -184,3 +184,46 @@ def test_tile_chain_lengths(tiles, shape):
     mant, expo = oracle.quantize(A)
     C_ref, T, _ = oracle.gemm(mant, expo, Bb)
     _check(_run(mant, expo, Bb, tiles), C_ref, T, f"chain {shape} {tiles}")
+
+
+def test_graph_capture_and_replay():
+    """The run call is a single kernel launch on the caller's stream, so a chain of GEMMs and quantisations can be
+    captured into a HIP graph (small problems are launch-bound).  Two layers, y = quantise(x W1) W2, captured once
+    and replayed three times with eager work in between; every replay must reproduce the eager result bit for bit."""
+    import torch
+    M, K, N1, N2 = 200, 264, 256, 136
+    A, W1b = workloads.make_inputs(workloads.CONFIGS["small256"], M=M, N=N1, K=K)
+    _, W2b = workloads.make_inputs(workloads.CONFIGS["ragged"], M=8, N=N2, K=N1)
+    x = atb.bfp16_quantize(torch.from_numpy(A).cuda())
+    W1 = bits_to_bf16_tensor(W1b, "cuda")
+    W2 = bits_to_bf16_tensor(W2b, "cuda")
+    g1 = atb.Gemm(M, N1, K, 32, 64, 64, 64, c_format="bfp16")      # its C is the BFP16 A operand of the second layer
+    g2 = atb.Gemm(M, N2, N1, 64, 128, 64, 128)
+    h = torch.empty(atb.bfp16_bytes(M, N1), dtype=torch.uint8, device="cuda")
+    y = torch.empty((M, N2), dtype=torch.bfloat16, device="cuda")
+
+    def layers():
+        g1.run(x, W1, h)
+        g2.run(h, W2, y)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        layers()                                # first launches outside the capture (occupancy queries, lazy loading)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    want = bf16_tensor_bits(y)
+    print("graph: capturing", flush=True)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        layers()
+    for rep in range(3):
+        h.fill_(0xAB)
+        y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        print(f"graph: replay {rep}", flush=True)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(bf16_tensor_bits(y), want), f"replay {rep} differs from the eager result"
+    g1.close()
+    g2.close()
