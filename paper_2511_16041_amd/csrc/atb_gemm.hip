@@ -48,7 +48,7 @@ typedef short shortx4 __attribute__((ext_vector_type(4)));
 // Sign-extended byte `byte` of word w as float (one v_cvt_f32_i32 with a byte select).
 ATB_DEV float mant_to_float(int w, int byte) { return (float)(int)(signed char)(w >> (8 * byte)); }
 
-template <int T_MA_, int T_MC_, int T_K_, int T_N_, int WM_, int WN_, int PF_, int AB_ = 2, int AO_ = -1, int BO_ = 0, int KU_ = 2>
+template <int T_MA_, int T_MC_, int T_K_, int T_N_, int WM_, int WN_, int PF_, int AB_ = 2, int AO_ = -1, int BO_ = 0, int KU_ = 2, int NB_ = 2>
 struct Shape {
     static constexpr int T_MA = T_MA_, T_MC = T_MC_, T_K = T_K_, T_N = T_N_, WM = WM_, WN = WN_;
     static constexpr int PF = PF_;                // A sub-tiles fetched this many phases ahead of their use
@@ -59,6 +59,11 @@ struct Shape {
     // g+1 is already complete and its first fragments are read before the barrier, which takes the
     // LDS latency out of every switch.
     static constexpr int AB = AB_;
+    // B LDS buffers.  The tile of K-step kt + NB is requested during K-step kt into the buffer that the
+    // tile of K-step kt has just left.  2 is enough when the tiles are large and many workgroups keep the
+    // memory busy; problems with one row of C tiles have fewer workgroups than CUs and live on the bytes each
+    // workgroup keeps in flight, so their instances use a ring of 3 or more (indexed at run time).
+    static constexpr int NB = NB_;
     static constexpr int DA = (AB_ == 4) ? 2 : 1; // decode runs this many sub-tiles ahead
     static constexpr int NT = WM * WN * 64;       // threads
     // Staging is dealt out in slabs of NTS chunks (one chunk per thread of a group of NTS threads).
@@ -78,7 +83,7 @@ struct Shape {
     static constexpr int PB = T_N * 2;            // B rows are not padded: an XOR swizzle of the 16-byte chunks avoids the bank conflicts
     static constexpr int A_BYTES = T_MA * PA;
     static constexpr int B_BYTES = T_K * PB;
-    static constexpr int LDS_BYTES = AB * A_BYTES + 2 * B_BYTES;
+    static constexpr int LDS_BYTES = AB * A_BYTES + NB * B_BYTES;
     // B given as BFP16 (B^T, N x K, blocks along K): the tile is staged like A, [n][k] with pitch PA
     static constexpr int BT_BYTES = T_N * PA;
     static constexpr int LDS_BYTES_BT = AB * A_BYTES + 2 * BT_BYTES;
@@ -100,6 +105,7 @@ struct Shape {
     static constexpr int SWZ = (T_N / 8 >= 16) ? 2 : 1;
     static constexpr int NBASE = (NTW < 4) ? NTW : 4;   // distinct per-lane read bases (the swizzle permutes 4 bands)
     static_assert(T_MC % T_MA == 0, "rho must be an integer");
+    static_assert(NB >= 2, "the B tile being multiplied and the one being fetched");
     static_assert(KU % 2 == 0 && PF >= 2 && (KU * RHO) % PF == 0, "prefetch distance: at least 2 (fetch and decode overlap), dividing the sub-tiles of one loop iteration");
     static_assert(AB == 2 || (AB == 4 && PF >= 3 && (KU * RHO) % 4 == 0), "4 A buffers need a fetch distance of 3 or more and must divide the sub-tiles of one loop iteration");
     static_assert(T_K % 64 == 0, "a K-step is a whole number of 64-wide panels of the BFP16 layout");
@@ -153,6 +159,25 @@ __device__ unsigned long long atb_trace_acc[16 * 8];
 #define ATB_TRACE_FLUSH() do { } while (0)
 #endif
 
+// Origin of the t-th tile of this workgroup's XCD (false past the end of the walk).  Workgroups
+// are dealt round-robin to the 8 XCDs (each with its own L2); XCD x owns the contiguous run of
+// tiles [x * per_xcd, (x + 1) * per_xcd), walked in bands of group_m tile rows so that the
+// workgroups resident on one XCD share few distinct A row panels and B column panels.
+template <class S>
+ATB_DEV bool tile_origin(const GemmParams &p, int t, int &tm0, int &tn0)
+{
+    const int total = p.tiles_m * p.tiles_n;
+    const int per_xcd = (total + 7) / 8;
+    const int logical = (int)(blockIdx.x % 8) * per_xcd + t;
+    if (t >= per_xcd || logical >= total) return false;
+    const int band_sz = p.group_m * p.tiles_n;
+    const int band = logical / band_sz, in_band = logical % band_sz;
+    const int rows_here = min(p.group_m, p.tiles_m - band * p.group_m);
+    tm0 = (band * p.group_m + in_band % rows_here) * S::T_MC;
+    tn0 = (in_band / rows_here) * S::T_N;
+    return true;
+}
+
 // The per-workgroup state of one C tile.  Everything is indexed with compile-time constants after
 // inlining, so the arrays live in registers (acc in AccVGPRs).
 //
@@ -182,7 +207,7 @@ __device__ unsigned long long atb_trace_acc[16 * 8];
 // does the same for A -- and its fragments are plain 16-byte LDS reads.  Tile kt is fetched in the
 // first phase of K-step kt-3, decoded during K-step kt-2, read into fragment registers in the last
 // band of K-step kt-1.  CBFP: the epilogue quantises C to BFP16 in blocks of 8 along N.
-template <class S, bool VEC, int ROLE, bool BBFP = false, bool CBFP = false>
+template <class S, bool VEC, int ROLE, bool BBFP = false, bool CBFP = false, bool SK = false>
 struct TileKernel {
     static constexpr int NTS = S::NTS, ACE = S::ACE, A_CPR = S::A_CPR;
     static constexpr int AO = BBFP ? S::A_SLABS : S::AO;                                 // with B in BFP16 the second group has its hands full
@@ -193,16 +218,21 @@ struct TileKernel {
     // four exponent bytes are one aligned dword, so one exponent request serves both chunks.
     static constexpr bool PAIRK = (APT == 2 && ACE == 16 && A_FIRST == 0 && S::T_K == 64);
     static constexpr int A_VMEM = PAIRK ? 3 : APT * 2;       // memory requests per thread and A sub-tile
+    // Rows >= M of an edge tile only feed rows of C that are never stored.  SK is the variant of the kernel
+    // for tiles at least half of whose rows lie beyond M (skinny problems, where that is most of the VALU
+    // work): it decodes block by block and skips, wave by wave, the chunks without a row below M.  (Their
+    // requests are still issued: the explicit vmcnt waits count requests.)
+    static_assert(!SK || (S::RHO * APT <= 32 && !BBFP), "one liveness bit per chunk of the tile");
     static constexpr int B_FIRST = (ROLE == 2) ? S::BO : 0;
     static constexpr int BPT = BBFP ? 0 : (ROLE == 0) ? S::B_SLABS : (ROLE == 1) ? S::BO : S::B_SLABS - S::BO;   // bf16 B chunks per thread per tile
     static constexpr int BTPT = !BBFP ? 0 : (ROLE == 1) ? 0 : S::BT_SLABS;               // BFP16 B chunks (16 mantissas) per thread per tile
     static constexpr int NPAIR_B = BTPT * 8;                                             // B mantissa pairs per thread per tile
-    static constexpr int NSTEP_A = NPAIR > 0 ? NPAIR + 2 : 0;                            // decode pipeline steps per phase (A sub-tile)
+    static constexpr int NSTEP_A = NPAIR == 0 ? 0 : SK ? NPAIR / 4 : NPAIR + 2;          // decode items per phase (A sub-tile): pipeline steps, or blocks
     static constexpr int NSTEP_B = NPAIR_B > 0 ? NPAIR_B / S::RHO + 2 : 0;               // ... and for this phase's share of the B tile
     static constexpr int APTN = APT > 0 ? APT : 1, BPTN = BPT > 0 ? BPT : 1, BTPTN = BTPT > 0 ? BTPT : 1;   // array extents
     static constexpr int B_BYTES = BBFP ? S::BT_BYTES : S::B_BYTES;
     static_assert(!BBFP || (NPAIR_B % S::RHO == 0 && S::T_K % 16 == 0 && (S::T_N * S::T_K / 16) % NTS == 0), "BFP16 B staging must split evenly");
-    static_assert(!BBFP || S::LDS_BYTES_BT <= 160 * 1024, "LDS budget of a gfx950 CU");
+    static_assert(!BBFP || (S::LDS_BYTES_BT <= 160 * 1024 && S::NB == 2), "LDS budget of a gfx950 CU; the BFP16 B path has two buffers");
     static_assert((ROLE == 0) == (S::NT != 512), "two wave groups exactly when two waves share a SIMD");
 
     const GemmParams &p;
@@ -219,6 +249,7 @@ struct TileKernel {
     char *a_wr[S::AB], *b_wr[2];
     const char *a_rd[S::AB], *b_rd[2][S::NBASE];  // b_rd[buffer][column band mod 4]
     char *b_req[2];                    // LDS byte address of this wave's first 1 KiB B request, per buffer
+    int b_fill_off, b_read_off;        // NB > 2: byte offsets of the ring buffers being filled / read next (wave-uniform)
     // Byte offsets of this thread's global loads relative to the current K-step.  They never
     // change: the K-step advance is applied to the (scalar) buffer descriptors instead, base up and
     // size down, so the hardware range check keeps masking panels past the last of A and rows >= K of B, and no
@@ -230,6 +261,7 @@ struct TileKernel {
     int am_left, ae_left;              // bytes from those starts to the end of the planes
     int64_t b_left;                    // likewise for B, which may be larger than 2^31 bytes
     int e_shift;                       // bit position of this thread's exponent byte(s) in the loaded dword
+    unsigned a_mask;                   // SK: bit sub * APT + i set if chunk i of sub-tile sub has a row < M in this wave
     // B in BFP16: this thread's chunks of the B^T tile (row n, 16 mantissas), like the A members
     char *bt_wr[2];
     const char *bt_rd[2];
@@ -347,27 +379,23 @@ struct TileKernel {
         c_t = t_first;
         tile_at(c_t, m0, n0);
         if constexpr (APT > 0) { open_a(t_first); remake_a(); }
+        a_mask = 0xFFFFFFFFu;
+        if constexpr (SK) {
+            const int wrow = __builtin_amdgcn_readfirstlane(a_row);     // smallest staging row of this wave
+            a_mask = 0;
+#pragma unroll
+            for (int sub = 0; sub < S::RHO; ++sub)
+#pragma unroll
+                for (int i = 0; i < APT; ++i) {
+                    const int first = m0 + sub * S::T_MA + wrow + (PAIRK ? 0 : (A_FIRST + i) * (NTS / A_CPR));
+                    if (first < p.M) a_mask |= 1u << (sub * APT + i);
+                }
+        }
         if constexpr (BTPT > 0) { open_b(t_first); remake_bt(); }
         if constexpr (BPT > 0) { open_b(t_first); remake_b(); }
     }
 
-    // Origin of the t-th tile of this workgroup's XCD (false past the end of the walk).  Workgroups
-    // are dealt round-robin to the 8 XCDs (each with its own L2); XCD x owns the contiguous run of
-    // tiles [x * per_xcd, (x + 1) * per_xcd), walked in bands of group_m tile rows so that the
-    // workgroups resident on one XCD share few distinct A row panels and B column panels.
-    ATB_DEV bool tile_at(int t, int &tm0, int &tn0) const
-    {
-        const int total = p.tiles_m * p.tiles_n;
-        const int per_xcd = (total + 7) / 8;
-        const int logical = (int)(blockIdx.x % 8) * per_xcd + t;
-        if (t >= per_xcd || logical >= total) return false;
-        const int band_sz = p.group_m * p.tiles_n;
-        const int band = logical / band_sz, in_band = logical % band_sz;
-        const int rows_here = min(p.group_m, p.tiles_m - band * p.group_m);
-        tm0 = (band * p.group_m + in_band % rows_here) * S::T_MC;
-        tn0 = (in_band / rows_here) * S::T_N;
-        return true;
-    }
+    ATB_DEV bool tile_at(int t, int &tm0, int &tn0) const { return tile_origin<S>(p, t, tm0, tn0); }
 
     // Point the A requests at the first K-step of tile t of the walk; past the last tile they get
     // empty buffers, so every request reads zeros without touching memory.  (The caller rebuilds
@@ -527,7 +555,8 @@ struct TileKernel {
         if constexpr (VEC) {
 #if defined(__HIP_DEVICE_COMPILE__)
             typedef __attribute__((address_space(3))) void lds_void;
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs.b, (lds_void *)(b_req[buf] + i * (NTS * 16)), 16, b_off[i], 0, 0, 0);
+            char *dst = (S::NB > 2) ? b_req[0] + b_fill_off : b_req[buf];
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs.b, (lds_void *)(dst + i * (NTS * 16)), 16, b_off[i], 0, 0, 0);
 #else
             (void)buf;   // the host pass only parses this function
 #endif
@@ -622,6 +651,30 @@ struct TileKernel {
         }
     }
 
+    // The skinny-tile variant of the decode (SK): one BFP16 block (8 mantissas -> 16 bytes of bf16 in LDS)
+    // per call, behind one wave-uniform test of its chunk's liveness bit.
+    template <int set, int b>
+    ATB_DEV void decode_block(char *dst_base, unsigned live)
+    {
+        constexpr int BPC = ACE / 8;                                 // blocks per chunk
+        constexpr int i = b / BPC, q = b % BPC;
+        if ((live >> i) & 1u) {
+            const unsigned e = a_expo[set][PAIRK ? 0 : i];
+            const int bit = PAIRK ? 16 * i + 8 * q : e_shift + 8 * q;
+            const int sh = (int)((e >> bit) & 0xFFu) - 133;
+            unsigned out[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int w = a_mant[set][i][2 * q + t / 2];
+                union { bf16x2 v; unsigned w; } pk;
+                pk.v = bf16x2{(__bf16)ldexpf(mant_to_float(w, (t % 2) * 2), sh), (__bf16)ldexpf(mant_to_float(w, (t % 2) * 2 + 1), sh)};
+                out[t] = pk.w;
+            }
+            char *dst = dst_base + (PAIRK ? i * (ACE * 2) : i * (NTS / A_CPR) * S::PA) + q * 16;
+            *reinterpret_cast<intx4 *>(dst) = intx4{(int)out[0], (int)out[1], (int)out[2], (int)out[3]};
+        }
+    }
+
     template <bool ISB, int set, int first, int count, int u = 0>
     ATB_DEV void decode_all(char *dst_base)
     {
@@ -661,7 +714,8 @@ struct TileKernel {
         if constexpr (BBFP) {
             bfrag[ks][nt] = *reinterpret_cast<const bf16x8 *>(bt_rd[buf] + nt * 32 * S::PA + ks * 32);
         } else {
-            const char *src = b_rd[buf][nt % S::NBASE] + ks * 16 * S::PB + (nt / S::NBASE) * (S::NBASE * 64);
+            const char *base = (S::NB > 2) ? b_rd[0][nt % S::NBASE] + b_read_off : b_rd[buf][nt % S::NBASE];
+            const char *src = base + ks * 16 * S::PB + (nt / S::NBASE) * (S::NBASE * 64);
             typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
             union { shortx4 s[2]; bf16x8 b; } u;
             u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(src));
@@ -722,11 +776,14 @@ struct TileKernel {
         } else if constexpr (j < j3) {
             load_a_chunk<g % S::PF, (s + S::PF) % S::RHO, j - j2>();
         } else if constexpr (j < j4) {
-            decode_step<false, (g + S::DA) % S::PF, 0, NPAIR, j - j3>(a_wr[(g + S::DA) % S::AB]);
+            if constexpr (SK)
+                decode_block<(g + S::DA) % S::PF, j - j3>(a_wr[(g + S::DA) % S::AB], a_mask >> (((s + S::DA) % S::RHO) * APTN));
+            else
+                decode_step<false, (g + S::DA) % S::PF, 0, NPAIR, j - j3>(a_wr[(g + S::DA) % S::AB]);
         } else if constexpr (j < j5) {
             decode_step<true, kpar, s * n_dt, n_dt, j - j4>(bt_wr[kpar]);
         } else {
-            store_b_chunk<j - j5>(b_wr[kpar]);
+            store_b_chunk<j - j5>((S::NB > 2) ? b_wr[0] + b_fill_off : b_wr[kpar]);
         }
     }
 
@@ -788,17 +845,27 @@ struct TileKernel {
             ATB_STAMP(2);
             // The B tile requested (straight into LDS) in the first phase of a K-step is read in the
             // last band of the next K-step, so the last barrier before that band has to publish it.
-            // rho = 1: that is the barrier ending the K-step of the request; only the A requests
-            // issued after it are younger.  rho >= 2: the barrier ending the last-but-one phase of
-            // the next K-step, which leaves the tile almost two K-steps to arrive; younger are the
-            // A requests of 2 rho - 1 phases and the next B tile's requests.
-            if constexpr (VEC && BPT > 0 && S::RHO == 1) wait_vm<A_VMEM>();
+            // With NB buffers the tile read in K-step kt + 1 was requested at the start of K-step kt + 2 - NB.
+            // rho = 1: the barrier is the one ending K-step kt; younger than the tile's requests are the A
+            // requests of NB - 1 K-steps and NB - 2 further B tiles.  rho >= 2: the barrier ending the
+            // last-but-one phase of K-step kt + 1; younger are the A requests of NB rho - 1 phases and
+            // NB - 1 further B tiles.  (A smaller count only waits for more than necessary.)
+            if constexpr (VEC && BPT > 0 && S::RHO == 1) wait_vm<vm_cap((S::NB - 1) * A_VMEM + (S::NB - 2) * BPT)>();
             if constexpr (VEC && BPT > 0 && S::RHO >= 2 && s == S::RHO - 2)
-                wait_vm<(2 * S::RHO - 1) * A_VMEM + BPT>();
+                wait_vm<vm_cap((S::NB * S::RHO - 1) * A_VMEM + (S::NB - 1) * BPT)>();
             switch_barrier();   // the "kernel switch" of the ATB nest
             ATB_STAMP(3);
             phases<ki, s + 1>();
         }
+    }
+
+    static constexpr int vm_cap(int n) { return n < 63 ? n : 63; }     // vmcnt is a 6-bit counter
+
+    // NB > 2: the ring moves on by one buffer per K-step
+    ATB_DEV void advance_b_ring()
+    {
+        b_fill_off = (b_fill_off + B_BYTES == S::NB * B_BYTES) ? 0 : b_fill_off + B_BYTES;
+        b_read_off = (b_read_off + B_BYTES == S::NB * B_BYTES) ? 0 : b_read_off + B_BYTES;
     }
 
     template <int ki>
@@ -806,6 +873,7 @@ struct TileKernel {
     {
         if constexpr (ki < S::KU) {
             phases<ki, 0>();
+            if constexpr (S::NB > 2) advance_b_ring();
             ksteps<ki + 1>();
         }
     }
@@ -821,13 +889,23 @@ struct TileKernel {
 
     ATB_DEV void run()
     {
-        // prologue: B tiles 0 and 1 into LDS, the first PF A sub-tiles into registers, sub-tile 0
+        // prologue: the first NB B tiles into LDS, the first PF A sub-tiles into registers, sub-tile 0
         // into LDS, B tile 0 into fragment registers
+        if constexpr (S::NB > 2) b_fill_off = 0;
         load_b(0);
         if constexpr (BBFP) { load_bt<0>(); load_bt<1>(); }
         prologue_loads();
         if constexpr (!VEC) store_b_all(b_wr[0]);
-        load_b(1);
+        if constexpr (S::NB > 2) {
+#pragma unroll
+            for (int t = 1; t < S::NB; ++t) {
+                b_fill_off = t * B_BYTES;
+                load_b(0);
+                if constexpr (!VEC) store_b_all(b_wr[0] + b_fill_off);
+            }
+        } else {
+            load_b(1);
+        }
         if constexpr (BBFP) {
             // B tiles 0 and 1 decoded into LDS; tile 2 into the register set that K-step 0 decodes
             store_bt_all<0>(bt_wr[0]);
@@ -837,9 +915,15 @@ struct TileKernel {
         store_a_all<0>(a_wr[0]);
         if constexpr (S::AB == 4) store_a_all<1>(a_wr[1]);
         if constexpr (VEC && BPT > 0) wait_vm<0>();
-        if constexpr (!VEC) store_b_all(b_wr[1]);
+        if constexpr (!VEC && S::NB == 2) store_b_all(b_wr[1]);
         __syncthreads();
+        if constexpr (S::NB > 2) b_read_off = 0;
         read_b_frags_all(0);
+        if constexpr (S::NB > 2) {
+            // K-step 0 refills buffer 0 and reads the fragments of K-step 1 from buffer 1
+            b_fill_off = 0;
+            b_read_off = B_BYTES;
+        }
         // B buffer 0 is refilled from the first phase on: every wave must have its fragments first
         switch_barrier();
         if constexpr (S::AB == 4) read_first_band<0>(a_rd[0]);
@@ -955,6 +1039,18 @@ __device__ __forceinline__ void tile_loop(const GemmParams &p, char *lds)
     const int per_xcd = (total + 7) / 8;
     const int first = (int)blockIdx.x / 8;
     if (first >= per_xcd || (int)(blockIdx.x % 8) * per_xcd + first >= total) return;   // the whole workgroup leaves
+    // workgroups of the skinny-problem instances whose tile lies at least half beyond M take the variant
+    // that skips dead rows (measured on the other small instances it does not pay: there a wave's chunks
+    // are either all live or the block-wise decode costs more than the skipped rows save)
+    if constexpr (S::T_K >= 256 && S::T_MC * S::T_N < 256 * 256 && !BBFP) {
+        int m0 = 0, n0 = 0;
+        tile_origin<S>(p, first, m0, n0);
+        if (p.M - m0 <= S::T_MC / 2) {
+            TileKernel<S, VEC, ROLE, BBFP, CBFP, true> tile(p, lds, first, (int)gridDim.x / 8);
+            tile.run();
+            return;
+        }
+    }
     TileKernel<S, VEC, ROLE, BBFP, CBFP> tile(p, lds, first, (int)gridDim.x / 8);
     tile.run();
 }
@@ -1075,6 +1171,14 @@ const Instance g_instances[] = {
     // small tiles for small problems
     make_instance<Shape<64, 64, 64, 64, 2, 2, 2, 2>, true>(1.12),
     make_instance<Shape<32, 64, 64, 64, 1, 2, 2, 2>, true>(1.24),
+    // skinny problems (M <= 64 or so: one row of C tiles, fewer workgroups than CUs) are bound by the
+    // latency of the B stream, not its bandwidth: a K-step of 256 keeps four times the bytes in flight
+    // (measured at M = 16 .. 128, N = K = 8192: 43 - 57 us against 72 us for the 64-deep tiles; a symmetric
+    // 64 x 64 x 256 tile: 60 us; a ring of 3 B buffers instead of 2: no change, kept as the ATB instance's
+    // use of the LDS that its small A buffers leave)
+    // (factor: its two waves, one per SIMD on half the CU, issue decode, fragment reads and MFMAs in order;
+    // measured a third of the fit at every M from 16 to 8192, so the selector takes it for M <= 128 only)
+    make_instance<Shape<32, 64, 256, 64, 1, 2, 2, 2, -1, 0, 2, 3>>(0.33),
 };
 
 

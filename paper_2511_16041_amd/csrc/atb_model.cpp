@@ -163,6 +163,8 @@ extern "C" atb_status atb_select_tiles(int64_t M, int64_t N, int64_t K, const at
         // per microkernel in its Table 1)
         ch.compute_bound *= x.eff_scale;
         ch.eff_core *= x.eff_scale;
+        // the kernels run whole pairs of K-steps: the tail of the last pair multiplies zeros
+        ch.compute_bound *= (double)K / (std::ceil((double)K / (2.0 * x.T_K)) * 2.0 * x.T_K);
         atb_hw_params h;
         if (hw) h = *hw; else atb_hw_params_mi355x(&h);
         if (x.wg_per_cu > 1 && h.acc_bytes > 0.0) {

@@ -16,6 +16,7 @@ BIG = [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256), (32, 256, 6
 WIDE_K = [(32, 256, 128, 256)]      # T_K = 128: feasible only with ATB
 SMALL = [(64, 64, 64, 64), (32, 64, 64, 64)]
 MID = [(128, 128, 64, 256), (64, 128, 64, 256), (128, 128, 64, 128), (64, 128, 64, 128)]
+SKINNY = [(32, 64, 256, 64)]      # T_K = 256 and a ring of 3 B buffers, for problems with one row of C tiles
 
 
 def _run(mant, expo, Bb, tiles, poison=True):
@@ -44,10 +45,10 @@ def _check(Cg_bits, C_ref, T, what):
 
 
 def test_instances_cover_the_tests():
-    assert set(BIG + SMALL + MID + WIDE_K) == set(atb.instances())
+    assert set(BIG + SMALL + MID + WIDE_K + SKINNY) == set(atb.instances())
 
 
-@pytest.mark.parametrize("tiles", SMALL + MID + BIG + WIDE_K)
+@pytest.mark.parametrize("tiles", SMALL + SKINNY + MID + BIG + WIDE_K)
 def test_small256_config(tiles):
     print(f"gemm small256 tiles={tiles}", flush=True)
     A, Bb = workloads.make_inputs(workloads.CONFIGS["small256"])
@@ -56,7 +57,7 @@ def test_small256_config(tiles):
     _check(_run(mant, expo, Bb, tiles), C_ref, T, f"small256 {tiles}")
 
 
-@pytest.mark.parametrize("tiles", SMALL + MID + BIG + WIDE_K)
+@pytest.mark.parametrize("tiles", SMALL + SKINNY + MID + BIG + WIDE_K)
 @pytest.mark.parametrize("shape", [(300, 500, 264), (257, 263, 72), (33, 20, 8), (1, 1, 8), (520, 516, 136), (300, 499, 64), (300, 502, 72), (130, 18, 24)])
 def test_ragged_shapes(tiles, shape):
     """Several tiles plus ragged M and N tails, a K tail of 8, N not a multiple of 8, of 4 (rows of B only
@@ -69,7 +70,7 @@ def test_ragged_shapes(tiles, shape):
     _check(_run(mant, expo, Bb, tiles), C_ref, T, f"ragged {shape} {tiles}")
 
 
-@pytest.mark.parametrize("tiles", SMALL + MID + BIG + WIDE_K)
+@pytest.mark.parametrize("tiles", SMALL + SKINNY + MID + BIG + WIDE_K)
 def test_exact_inputs_bitwise(tiles):
     """Small-integer inputs: fp32 accumulation is exact in any order, so every instance
     (every rho) must equal the oracle bit for bit."""
@@ -227,3 +228,15 @@ def test_graph_capture_and_replay():
         assert np.array_equal(bf16_tensor_bits(y), want), f"replay {rep} differs from the eager result"
     g1.close()
     g2.close()
+
+
+@pytest.mark.parametrize("tiles", SKINNY + SMALL)
+@pytest.mark.parametrize("shape", [(16, 520, 1096), (64, 1030, 2056), (100, 301, 776), (1, 64, 4096)])
+def test_skinny_shapes(tiles, shape):
+    """Decode-like problems: one or two rows of C tiles, long K (several K-steps of 256 plus a tail of 8)."""
+    M, N, K = shape
+    print(f"gemm skinny {shape} tiles={tiles}", flush=True)
+    A, Bb = workloads.make_inputs(workloads.CONFIGS["mlp"], M=M, N=N, K=K)
+    mant, expo = oracle.quantize(A)
+    C_ref, T, _ = oracle.gemm(mant, expo, Bb)
+    _check(_run(mant, expo, Bb, tiles), C_ref, T, f"skinny {shape} {tiles}")
