@@ -1165,7 +1165,7 @@ const Instance g_instances[] = {
     // share a CU overlap each other's barriers and latencies, which the per-tile formula does not see;
     // the symmetric 128 x 256 tile has a single barrier per short K-step and waits for its B tile there)
     make_instance<Shape<128, 128, 64, 256, 2, 4, 2, 2>, true>(0.47),
-    make_instance<Shape<64, 128, 64, 256, 2, 4, 4, 2>, true>(0.84),
+    make_instance<Shape<64, 128, 64, 256, 2, 4, 4, 2>, true>(0.88),
     make_instance<Shape<128, 128, 64, 128, 2, 2, 2, 2>, true>(0.95),
     make_instance<Shape<64, 128, 64, 128, 2, 2, 4, 2>, true>(0.95),
     // small tiles for small problems

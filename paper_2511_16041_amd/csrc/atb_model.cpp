@@ -26,17 +26,27 @@ namespace {
 
 // Share of the chip's full-load throughput that `tiles` equal tiles reach when `slots` of them run at a
 // time.  Full rounds count 1 each.  A last round that fills only a fraction f of the slots leaves CUs
-// idle, and the chip, which is power-limited under this kernel, clocks the busy ones higher: measured
-// on MI355X, a round at f = 1/2 runs 1.37 x faster per tile than a full one and the gain saturates near
-// 1.5 x (2 x when several workgroups share a CU, where a lone workgroup also has the CU to itself);
-// f^-1/2, capped, fits both.
+// (or places on a CU) idle, and its workgroups run faster than in a full round: the chip is power-limited
+// under this kernel and clocks the busy CUs higher, and a workgroup with fewer neighbours on its CU has
+// more of the CU's issue slots and LDS to itself.  Measured on MI355X (N = 2048 shapes, every instance):
+// the gain per workgroup follows f^-3/4 up to a cap that depends on how many workgroups share a CU at full
+// load (lone_speedup below).
 double round_efficiency(double tiles, double slots, double cap)
 {
     const double full = std::floor(tiles / slots);
     const double f = (tiles - full * slots) / slots;
     double time = full;
-    if (f > 0.0) time += 1.0 / std::min(cap, 1.0 / std::sqrt(f));
+    if (f > 0.0) time += 1.0 / std::min(cap, std::pow(f, -0.75));
     return (tiles / slots) / time;
+}
+
+// Largest gain of a workgroup in a sparsely filled round over a full one, by workgroups per CU at full
+// load: 1.4 for one per CU (the clock alone: 1.33 - 1.39 measured at f = 1/8 .. 1/2), 1.6 for two
+// (128 x 128 x 64 x 128 at f = 1/4: 1.62), 2.5 for three (64 x 128 x 64 x 128 at f = 1/6: 2.55), about
+// 2 for four and more (64 x 64 tiles: 1.6 - 1.95 at f = 1/2, 2.0 at f = 1/3).
+double lone_speedup(int wg_per_cu)
+{
+    return wg_per_cu <= 1 ? 1.4 : wg_per_cu == 2 ? 1.62 : wg_per_cu == 3 ? 2.5 : 2.05;
 }
 
 // Fixed cost of one launch (measured: a 256^3 problem takes 8 us whatever the tile).
@@ -137,7 +147,7 @@ extern "C" atb_status atb_model_eval(int64_t M, int64_t N, int64_t K, int T_MA, 
         // that hang over the matrix edge compute on padding.
         const double tm = std::ceil((double)M / T_MC), tn = std::ceil((double)N / T_N);
         const double useful = ((double)M * (double)N) / (tm * T_MC * tn * T_N);
-        r.compute_bound *= round_efficiency(tm * tn, hw.n_core, 1.5) * useful;
+        r.compute_bound *= round_efficiency(tm * tn, hw.n_core, lone_speedup(1)) * useful;
     }
     r.pred_flops = std::min(r.mem_bound, r.compute_bound);
     if (c_in_regs) {
@@ -171,7 +181,7 @@ extern "C" atb_status atb_select_tiles(int64_t M, int64_t N, int64_t K, const at
             // several workgroups share a CU: redo the round quantisation that atb_model_eval applied
             // for one workgroup per CU
             const double tiles = std::ceil((double)M / x.T_MC) * std::ceil((double)N / x.T_N);
-            ch.compute_bound *= round_efficiency(tiles, (double)h.n_core * x.wg_per_cu, 2.0) / round_efficiency(tiles, h.n_core, 1.5);
+            ch.compute_bound *= round_efficiency(tiles, (double)h.n_core * x.wg_per_cu, lone_speedup(x.wg_per_cu)) / round_efficiency(tiles, h.n_core, lone_speedup(1));
         }
         ch.pred_flops = std::min(ch.mem_bound, ch.compute_bound);
         if (h.acc_bytes > 0.0) {
