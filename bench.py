@@ -272,7 +272,9 @@ def main():
                 Cd = torch.empty((Mx, Nx), dtype=torch.bfloat16, device="cuda")
                 pick = atb.select_tiles(Mx, Nx, Kx)[0]
                 p = atb.Gemm(Mx, Nx, Kx, *pick.tiles())
-                _, kms = time_plan(p, Ab, Bd, Cd, 50, 10)
+                # short launches after a pause for host-side data generation: warm up for a few tens of ms, as the
+                # clock takes that long to settle (the headline's 50 warm-up launches of 0.9 ms do the same)
+                _, kms = time_plan(p, Ab, Bd, Cd, 200, 300)
                 p.close()
                 scaling.append({"M": Mx, "K": Kx, "N": Nx, "tiles": list(pick.tiles()),
                                 "tflops": round(2.0 * Mx * Nx * Kx / (kms * 1e-3) / 1e12, 1),
