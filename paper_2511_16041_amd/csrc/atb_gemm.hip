@@ -1124,10 +1124,11 @@ hipError_t launch_instance_fmt(const GemmParams &p, int b_format, int c_format, 
 }
 
 template <class S, bool FMT = false>
-Instance make_instance(double eff_scale = 1.0)
+Instance make_instance(double eff_scale = 1.0, double lone_cap = 0.0)
 {
     Instance i;
     i.eff_scale = eff_scale;
+    i.lone_cap = lone_cap;
     i.T_MA = S::T_MA;
     i.T_MC = S::T_MC;
     i.T_K = S::T_K;
@@ -1168,6 +1169,10 @@ const Instance g_instances[] = {
     make_instance<Shape<64, 128, 64, 256, 2, 4, 4, 2>, true>(0.88),
     make_instance<Shape<128, 128, 64, 128, 2, 2, 2, 2>, true>(0.95),
     make_instance<Shape<64, 128, 64, 128, 2, 2, 4, 2>, true>(0.95),
+    // T_K = 128 at 128 x 128 with ATB (one workgroup per CU): the best instance when the problem has about one
+    // such tile per CU (M = N = 2048: 617 - 778 TFLOP/s against 577 - 726); its workgroups gain nothing from
+    // idle neighbours (measured at half occupancy), hence the cap of 1
+    make_instance<Shape<64, 128, 128, 128, 2, 2, 4, 2>, true>(0.75, 1.0),
     // small tiles for small problems
     make_instance<Shape<64, 64, 64, 64, 2, 2, 2, 2>, true>(1.12),
     make_instance<Shape<32, 64, 64, 64, 1, 2, 2, 2>, true>(1.24),

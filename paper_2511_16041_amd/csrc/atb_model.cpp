@@ -177,11 +177,12 @@ extern "C" atb_status atb_select_tiles(int64_t M, int64_t N, int64_t K, const at
         ch.compute_bound *= (double)K / (std::ceil((double)K / (2.0 * x.T_K)) * 2.0 * x.T_K);
         atb_hw_params h;
         if (hw) h = *hw; else atb_hw_params_mi355x(&h);
-        if (x.wg_per_cu > 1 && h.acc_bytes > 0.0) {
-            // several workgroups share a CU: redo the round quantisation that atb_model_eval applied
-            // for one workgroup per CU
+        if ((x.wg_per_cu > 1 || x.lone_cap > 0.0) && h.acc_bytes > 0.0) {
+            // several workgroups share a CU, or the instance has a measured cap of its own: redo the round
+            // quantisation that atb_model_eval applied for one workgroup per CU
             const double tiles = std::ceil((double)M / x.T_MC) * std::ceil((double)N / x.T_N);
-            ch.compute_bound *= round_efficiency(tiles, (double)h.n_core * x.wg_per_cu, lone_speedup(x.wg_per_cu)) / round_efficiency(tiles, h.n_core, lone_speedup(1));
+            const double cap = x.lone_cap > 0.0 ? x.lone_cap : lone_speedup(x.wg_per_cu);
+            ch.compute_bound *= round_efficiency(tiles, (double)h.n_core * x.wg_per_cu, cap) / round_efficiency(tiles, h.n_core, lone_speedup(1));
         }
         ch.pred_flops = std::min(ch.mem_bound, ch.compute_bound);
         if (h.acc_bytes > 0.0) {
