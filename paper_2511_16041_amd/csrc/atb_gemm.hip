@@ -48,7 +48,7 @@ typedef short shortx4 __attribute__((ext_vector_type(4)));
 // Sign-extended byte `byte` of word w as float (one v_cvt_f32_i32 with a byte select).
 ATB_DEV float mant_to_float(int w, int byte) { return (float)(int)(signed char)(w >> (8 * byte)); }
 
-template <int T_MA_, int T_MC_, int T_K_, int T_N_, int WM_, int WN_, int PF_, int AB_ = 2, int AO_ = -1, int BO_ = 0, int KU_ = 2, int NB_ = 2>
+template <int T_MA_, int T_MC_, int T_K_, int T_N_, int WM_, int WN_, int PF_, int AB_ = 2, int AO_ = -1, int BO_ = 0, int KU_ = 2, int NB_ = 2, int HW_ = 0>
 struct Shape {
     static constexpr int T_MA = T_MA_, T_MC = T_MC_, T_K = T_K_, T_N = T_N_, WM = WM_, WN = WN_;
     static constexpr int PF = PF_;                // A sub-tiles fetched this many phases ahead of their use
@@ -65,11 +65,16 @@ struct Shape {
     // workgroup keeps in flight, so their instances use a ring of 3 or more (indexed at run time).
     static constexpr int NB = NB_;
     static constexpr int DA = (AB_ == 4) ? 2 : 1; // decode runs this many sub-tiles ahead
-    static constexpr int NT = WM * WN * 64;       // threads
+    static constexpr int CW = WM * WN;            // waves that multiply: a WM x WN grid over the C tile
+    // Helper waves.  Small tiles have few wave tiles (a 64 x 64 tile at T_MA = 32 feeds a 1 x 2 grid), and a
+    // wave that stages, decodes and multiplies issues all of it in order.  With HW > 0 the staging (requests,
+    // decode, LDS stores) moves to HW extra waves on the CU's other SIMDs and the CW waves only multiply.
+    static constexpr int HW = HW_;
+    static constexpr int NT = (CW + HW) * 64;     // threads
     // Staging is dealt out in slabs of NTS chunks (one chunk per thread of a group of NTS threads).
     // 8-wave workgroups run two waves per SIMD and form two groups, waves 0-3 and 4-7; the first
     // group stages A slabs [0, AO) and B slabs [0, BO) of every (sub-)tile, the second the rest.
-    static constexpr int NTS = (NT == 512) ? 256 : NT;
+    static constexpr int NTS = (HW > 0) ? HW * 64 : (CW == 8) ? 256 : CW * 64;
     static constexpr int RHO = T_MC / T_MA;
     static constexpr int MT = T_MC / 32;          // 32-row bands in the C tile
     static constexpr int SMT = T_MA / 32;         // bands per A sub-tile
@@ -211,8 +216,9 @@ template <class S, bool VEC, int ROLE, bool BBFP = false, bool CBFP = false, boo
 struct TileKernel {
     static constexpr int NTS = S::NTS, ACE = S::ACE, A_CPR = S::A_CPR;
     static constexpr int AO = BBFP ? S::A_SLABS : S::AO;                                 // with B in BFP16 the second group has its hands full
+    static constexpr bool COMPUTE = (ROLE != 3);                                         // ROLE 3: helper waves (stage everything, multiply nothing); ROLE 4: their partners (multiply only)
     static constexpr int A_FIRST = (ROLE == 2) ? AO : 0;                                 // first A slab of this wave group
-    static constexpr int APT = (ROLE == 0) ? S::A_SLABS : (ROLE == 1) ? AO : S::A_SLABS - AO;   // A chunks per thread per sub-tile
+    static constexpr int APT = (ROLE == 0 || ROLE == 3) ? S::A_SLABS : (ROLE == 1) ? AO : (ROLE == 2) ? S::A_SLABS - AO : 0;   // A chunks per thread per sub-tile
     static constexpr int NPAIR = APT * ACE / 2;                                          // mantissa pairs per thread per sub-tile
     // A thread with two 16-mantissa chunks takes them side by side in one row (32 consecutive k): their
     // four exponent bytes are one aligned dword, so one exponent request serves both chunks.
@@ -224,8 +230,8 @@ struct TileKernel {
     // requests are still issued: the explicit vmcnt waits count requests.)
     static_assert(!SK || (S::RHO * APT <= 32 && !BBFP), "one liveness bit per chunk of the tile");
     static constexpr int B_FIRST = (ROLE == 2) ? S::BO : 0;
-    static constexpr int BPT = BBFP ? 0 : (ROLE == 0) ? S::B_SLABS : (ROLE == 1) ? S::BO : S::B_SLABS - S::BO;   // bf16 B chunks per thread per tile
-    static constexpr int BTPT = !BBFP ? 0 : (ROLE == 1) ? 0 : S::BT_SLABS;               // BFP16 B chunks (16 mantissas) per thread per tile
+    static constexpr int BPT = BBFP ? 0 : (ROLE == 0 || ROLE == 3) ? S::B_SLABS : (ROLE == 1) ? S::BO : (ROLE == 2) ? S::B_SLABS - S::BO : 0;   // bf16 B chunks per thread per tile
+    static constexpr int BTPT = !BBFP ? 0 : (ROLE == 1 || ROLE == 4) ? 0 : S::BT_SLABS;               // BFP16 B chunks (16 mantissas) per thread per tile
     static constexpr int NPAIR_B = BTPT * 8;                                             // B mantissa pairs per thread per tile
     static constexpr int NSTEP_A = NPAIR == 0 ? 0 : SK ? NPAIR / 4 : NPAIR + 2;          // decode items per phase (A sub-tile): pipeline steps, or blocks
     static constexpr int NSTEP_B = NPAIR_B > 0 ? NPAIR_B / S::RHO + 2 : 0;               // ... and for this phase's share of the B tile
@@ -233,7 +239,8 @@ struct TileKernel {
     static constexpr int B_BYTES = BBFP ? S::BT_BYTES : S::B_BYTES;
     static_assert(!BBFP || (NPAIR_B % S::RHO == 0 && S::T_K % 16 == 0 && (S::T_N * S::T_K / 16) % NTS == 0), "BFP16 B staging must split evenly");
     static_assert(!BBFP || (S::LDS_BYTES_BT <= 160 * 1024 && S::NB == 2), "LDS budget of a gfx950 CU; the BFP16 B path has two buffers");
-    static_assert((ROLE == 0) == (S::NT != 512), "two wave groups exactly when two waves share a SIMD");
+    static_assert((ROLE == 0) == (S::CW != 8 && S::HW == 0) && (ROLE >= 3) == (S::HW > 0), "two staging groups exactly when two waves share a SIMD; helper roles exactly with helper waves");
+    static_assert(S::HW == 0 || !BBFP, "helper waves stage a bf16 B only");
 
     const GemmParams &p;
     Rsrc rs;
@@ -811,8 +818,9 @@ struct TileKernel {
             constexpr int nside = n_side<s>();
             constexpr int g = ki * S::RHO + s;
             constexpr int par = (g * S::PER + il) % 2;            // which half of afrag this band uses
-            acc[local][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag[ks][nt], afrag[par][ks],
-                                                                    acc[local][nt], 0, 0, 0);
+            if constexpr (COMPUTE)
+                acc[local][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag[ks][nt], afrag[par][ks],
+                                                                        acc[local][nt], 0, 0, 0);
             ATB_FENCE();
             // the last eighth of the slots carries no side work, so that the LDS stores of the decode
             // have drained when the wave reaches the switch barrier
@@ -820,13 +828,13 @@ struct TileKernel {
             constexpr int j0 = (m * nside) / NS < nside ? (m * nside) / NS : nside;
             constexpr int j1 = ((m + 1) * nside) / NS < nside ? ((m + 1) * nside) / NS : nside;
             side_range<ki, s, j0, j1>();
-            if constexpr (nt == S::NTW - 1) {
+            if constexpr (nt == S::NTW - 1 && COMPUTE) {
                 if constexpr (il + 1 < S::PER)
                     read_a_frag<par ^ 1, il + 1, ks>(a_rd[g % S::AB]);
                 else if constexpr (S::AB == 4)      // first band of the next sub-tile, already complete in LDS
                     read_a_frag<par ^ 1, 0, ks>(a_rd[(g + 1) % S::AB]);
             }
-            if constexpr (last_phase && il + 1 == S::PER) read_b_frag<ks, nt>(kpar ^ 1);
+            if constexpr (last_phase && il + 1 == S::PER && COMPUTE) read_b_frag<ks, nt>(kpar ^ 1);
             ATB_FENCE();
             slots<ki, s, m + 1>();
         }
@@ -838,7 +846,7 @@ struct TileKernel {
     {
         if constexpr (s < S::RHO) {
             constexpr int g = ki * S::RHO + s;
-            if constexpr (S::AB == 2) read_first_band<(g * S::PER) % 2>(a_rd[g % 2]);
+            if constexpr (S::AB == 2 && COMPUTE) read_first_band<(g * S::PER) % 2>(a_rd[g % 2]);
             ATB_FENCE();
             ATB_STAMP(1);
             slots<ki, s, 0>();
@@ -918,7 +926,7 @@ struct TileKernel {
         if constexpr (!VEC && S::NB == 2) store_b_all(b_wr[1]);
         __syncthreads();
         if constexpr (S::NB > 2) b_read_off = 0;
-        read_b_frags_all(0);
+        if constexpr (COMPUTE) read_b_frags_all(0);
         if constexpr (S::NB > 2) {
             // K-step 0 refills buffer 0 and reads the fragments of K-step 1 from buffer 1
             b_fill_off = 0;
@@ -926,7 +934,7 @@ struct TileKernel {
         }
         // B buffer 0 is refilled from the first phase on: every wave must have its fragments first
         switch_barrier();
-        if constexpr (S::AB == 4) read_first_band<0>(a_rd[0]);
+        if constexpr (S::AB == 4 && COMPUTE) read_first_band<0>(a_rd[0]);
 
         // The number of K-steps is rounded up to a whole loop body: the extra steps multiply by B rows
         // >= K, which read as zero.  The last K-steps of a tile already request, decode and stage the
@@ -935,7 +943,7 @@ struct TileKernel {
         ATB_STAMP(0);
         for (;;) {
             for (int kt = 0; kt < kt_steps; kt += S::KU) ksteps<0>();
-            if constexpr (CBFP) store_c_bfp(); else store_c();
+            if constexpr (!COMPUTE) { } else if constexpr (CBFP) store_c_bfp(); else store_c();
             c_t += t_stride;
             if (!tile_at(c_t, m0, n0)) break;
 #pragma unroll
@@ -1059,7 +1067,12 @@ template <class S, bool VEC, bool BBFP = false, bool CBFP = false>
 __global__ void __launch_bounds__(S::NT) atb_gemm_kernel(const GemmParams p)
 {
     __shared__ __attribute__((aligned(16))) char lds[BBFP ? S::LDS_BYTES_BT : S::LDS_BYTES];
-    if constexpr (S::NT == 512) {
+    if constexpr (S::HW > 0) {
+        if (threadIdx.x < S::CW * 64)
+            tile_loop<S, VEC, 4, BBFP, CBFP>(p, lds);
+        else
+            tile_loop<S, VEC, 3, BBFP, CBFP>(p, lds);
+    } else if constexpr (S::CW == 8) {
         // wave-uniform branch; both sides execute the same sequence of barriers
         if (threadIdx.x < 256)
             tile_loop<S, VEC, 1, BBFP, CBFP>(p, lds);
@@ -1178,12 +1191,13 @@ const Instance g_instances[] = {
     make_instance<Shape<32, 64, 64, 64, 1, 2, 2, 2>, true>(1.24),
     // skinny problems (M <= 64 or so: one row of C tiles, fewer workgroups than CUs) are bound by the
     // latency of the B stream, not its bandwidth: a K-step of 256 keeps four times the bytes in flight
-    // (measured at M = 16 .. 128, N = K = 8192: 43 - 57 us against 72 us for the 64-deep tiles; a symmetric
+    // (measured at M = 16 .. 128, N = K = 8192 before the helper waves: 43 - 57 us against 72 us for the 64-deep tiles; a symmetric
     // 64 x 64 x 256 tile: 60 us; a ring of 3 B buffers instead of 2: no change, kept as the ATB instance's
     // use of the LDS that its small A buffers leave)
-    // (factor: its two waves, one per SIMD on half the CU, issue decode, fragment reads and MFMAs in order;
-    // measured a third of the fit at every M from 16 to 8192, so the selector takes it for M <= 128 only)
-    make_instance<Shape<32, 64, 256, 64, 1, 2, 2, 2, -1, 0, 2, 3>>(0.33),
+    // Its 1 x 2 wave grid would leave two SIMDs idle and issue decode, fragment reads and MFMAs in one
+    // in-order stream per wave: four helper waves take the staging instead (48 -> 38 us at M = 64; two
+    // helpers: 48 us, eight: 37 us).  Factor: measured 0.42 - 0.49 of the fit from M = 16 to 8192.
+    make_instance<Shape<32, 64, 256, 64, 1, 2, 2, 2, -1, 0, 2, 3, 4>>(0.46),
 };
 
 
