@@ -21,6 +21,7 @@
 //   * one workgroup barrier per sub-tile is the "kernel switch" of Sec. 5;
 //   * workgroups of 8 waves (two per SIMD) split the staging by kind: waves 0-3 stage A, waves 4-7
 //     stage B (see TileKernel); the grid of the 256 x 256 tiles is persistent (see tile_loop).
+//     Smaller tiles have a grid of 4 or 2 multiplying waves plus as many helper waves that do the staging.
 // T_MA == T_MC is the symmetric baseline: same code, one sub-tile per K-step.
 // B may also arrive as BFP16 (as B^T, blocks along K) and C may be written as BFP16 (Sec. 6.1's
 // all-BFP16 storage); see the BBFP / CBFP template flags of TileKernel.
@@ -205,6 +206,9 @@ ATB_DEV bool tile_origin(const GemmParams &p, int t, int &tm0, int &tn0)
 // on alone, slowly).  There the staging work is split by kind instead of evenly: ROLE 1 (waves 0-3)
 // fetches, decodes and stores all of A, ROLE 2 (waves 4-7) requests all of B, which costs it a few
 // memory instructions and no arithmetic, so both waves of a SIMD reach the barrier together.
+// Tiles with fewer than eight wave tiles (Shape::HW > 0) use the same idea the other way round: ROLE 4
+// (the WM x WN grid of waves) only reads fragments and multiplies, ROLE 3 (HW helper waves) stages all of
+// A and B and multiplies nothing; both execute the same sequence of barriers.
 //
 // Storage formats (Sec. 6.1 lists the paper's precision configurations).  BBFP: B arrives as BFP16,
 // given as B^T (N x K, blocks along K, the same layout as A); its tile is fetched into registers,
@@ -240,7 +244,6 @@ struct TileKernel {
     static_assert(!BBFP || (NPAIR_B % S::RHO == 0 && S::T_K % 16 == 0 && (S::T_N * S::T_K / 16) % NTS == 0), "BFP16 B staging must split evenly");
     static_assert(!BBFP || (S::LDS_BYTES_BT <= 160 * 1024 && S::NB == 2), "LDS budget of a gfx950 CU; the BFP16 B path has two buffers");
     static_assert((ROLE == 0) == (S::CW != 8 && S::HW == 0) && (ROLE >= 3) == (S::HW > 0), "two staging groups exactly when two waves share a SIMD; helper roles exactly with helper waves");
-    static_assert(S::HW == 0 || !BBFP, "helper waves stage a bf16 B only");
 
     const GemmParams &p;
     Rsrc rs;
@@ -1180,15 +1183,11 @@ const Instance g_instances[] = {
     // the symmetric 128 x 256 tile has a single barrier per short K-step and waits for its B tile there)
     make_instance<Shape<128, 128, 64, 256, 2, 4, 2, 2>, true>(0.47),
     make_instance<Shape<64, 128, 64, 256, 2, 4, 4, 2>, true>(0.88),
-    make_instance<Shape<128, 128, 64, 128, 2, 2, 2, 2>, true>(0.95),
-    make_instance<Shape<64, 128, 64, 128, 2, 2, 4, 2>, true>(0.95),
-    // T_K = 128 at 128 x 128 with ATB (one workgroup per CU): the best instance when the problem has about one
-    // such tile per CU (M = N = 2048: 617 - 778 TFLOP/s against 577 - 726); its workgroups gain nothing from
-    // idle neighbours (measured at half occupancy), hence the cap of 1
-    make_instance<Shape<64, 128, 128, 128, 2, 2, 4, 2>, true>(0.75, 1.0),
+    make_instance<Shape<128, 128, 64, 128, 2, 2, 2, 2, -1, 0, 2, 2, 4>, true>(1.06),
+    make_instance<Shape<64, 128, 64, 128, 2, 2, 4, 2, -1, 0, 2, 2, 4>, true>(1.08),
     // small tiles for small problems
-    make_instance<Shape<64, 64, 64, 64, 2, 2, 2, 2>, true>(1.12),
-    make_instance<Shape<32, 64, 64, 64, 1, 2, 2, 2>, true>(1.24),
+    make_instance<Shape<64, 64, 64, 64, 2, 2, 2, 2, -1, 0, 2, 2, 4>, true>(1.2),
+    make_instance<Shape<32, 64, 64, 64, 1, 2, 2, 2, -1, 0, 2, 2, 2>, true>(1.24),
     // skinny problems (M <= 64 or so: one row of C tiles, fewer workgroups than CUs) are bound by the
     // latency of the B stream, not its bandwidth: a K-step of 256 keeps four times the bytes in flight
     // (measured at M = 16 .. 128, N = K = 8192 before the helper waves: 43 - 57 us against 72 us for the 64-deep tiles; a symmetric

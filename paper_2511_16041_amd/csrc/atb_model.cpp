@@ -30,23 +30,24 @@ namespace {
 // under this kernel and clocks the busy CUs higher, and a workgroup with fewer neighbours on its CU has
 // more of the CU's issue slots and LDS to itself.  Measured on MI355X (N = 2048 shapes, every instance):
 // the gain per workgroup follows f^-3/4 up to a cap that depends on how many workgroups share a CU at full
-// load (lone_speedup below).
-double round_efficiency(double tiles, double slots, double cap)
+// load (lone_speedup below); with four or more workgroups per CU it follows 1/f, i.e. a half-filled round of
+// small tiles takes half the time.
+double round_efficiency(double tiles, double slots, double cap, double exponent = 0.75)
 {
     const double full = std::floor(tiles / slots);
     const double f = (tiles - full * slots) / slots;
     double time = full;
-    if (f > 0.0) time += 1.0 / std::min(cap, std::pow(f, -0.75));
+    if (f > 0.0) time += 1.0 / std::min(cap, std::pow(f, -exponent));
     return (tiles / slots) / time;
 }
 
 // Largest gain of a workgroup in a sparsely filled round over a full one, by workgroups per CU at full
-// load: 1.4 for one per CU (the clock alone: 1.33 - 1.39 measured at f = 1/8 .. 1/2), 1.6 for two
-// (128 x 128 x 64 x 128 at f = 1/4: 1.62), 2.5 for three (64 x 128 x 64 x 128 at f = 1/6: 2.55), about
-// 2 for four and more (64 x 64 tiles: 1.6 - 1.95 at f = 1/2, 2.0 at f = 1/3).
+// load: 1.4 for one per CU (the clock alone: 1.33 - 1.39 measured at f = 1/8 .. 1/2), 2.1 for two
+// (128 x 128 x 64 x 128 at f = 1/4), 3.0 for three (64 x 128 x 64 x 128 at f = 1/6), about 2 for four and
+// more (64 x 64 tiles: 2.0 - 2.1 at f = 1/2 and at f = 1/3).
 double lone_speedup(int wg_per_cu)
 {
-    return wg_per_cu <= 1 ? 1.4 : wg_per_cu == 2 ? 1.62 : wg_per_cu == 3 ? 2.5 : 2.05;
+    return wg_per_cu <= 1 ? 1.4 : wg_per_cu == 2 ? 2.1 : wg_per_cu == 3 ? 3.0 : 2.05;
 }
 
 // Fixed cost of one launch (measured: a 256^3 problem takes 8 us whatever the tile).
@@ -182,7 +183,7 @@ extern "C" atb_status atb_select_tiles(int64_t M, int64_t N, int64_t K, const at
             // quantisation that atb_model_eval applied for one workgroup per CU
             const double tiles = std::ceil((double)M / x.T_MC) * std::ceil((double)N / x.T_N);
             const double cap = x.lone_cap > 0.0 ? x.lone_cap : lone_speedup(x.wg_per_cu);
-            ch.compute_bound *= round_efficiency(tiles, (double)h.n_core * x.wg_per_cu, cap) / round_efficiency(tiles, h.n_core, lone_speedup(1));
+            ch.compute_bound *= round_efficiency(tiles, (double)h.n_core * x.wg_per_cu, cap, x.wg_per_cu >= 4 ? 1.0 : 0.75) / round_efficiency(tiles, h.n_core, lone_speedup(1));
         }
         ch.pred_flops = std::min(ch.mem_bound, ch.compute_bound);
         if (h.acc_bytes > 0.0) {

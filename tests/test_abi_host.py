@@ -177,7 +177,8 @@ def test_create_fmt_validation():
 def test_selector_tracks_problem_size():
     """Few C tiles: smaller tiles fill the chip better (the N = 2048 shapes of the paper's Table 3)."""
     assert atb.select_tiles(8192, 8192, 8192)[0].T_MC == 256
-    assert atb.select_tiles(4096, 2048, 4096)[0].tiles()[1:] == (128, 64, 256)
+    assert atb.select_tiles(4096, 2048, 4096)[0].T_MC == 128         # 128 x 256 and 128 x 128 tiles measure within 3 % of each other here
+    assert atb.select_tiles(1024, 2048, 8192)[0].T_MC == 64
     assert atb.select_tiles(1024, 2048, 4096)[0].T_MC <= 128
     assert atb.select_tiles(1024, 2048, 4096)[0].T_N <= 128
     # a launch never beats its fixed cost, and predictions grow with the problem
