@@ -1180,7 +1180,8 @@ const Instance g_instances[] = {
     // shapes of the paper's Table 3): 128 x 256 on 8 waves, 128 x 128 on 4 waves (two workgroups per CU)
     // (the factors are measured full-load throughput over the 256 x 256 family's fit: workgroups that
     // share a CU overlap each other's barriers and latencies, which the per-tile formula does not see;
-    // the symmetric 128 x 256 tile has a single barrier per short K-step and waits for its B tile there)
+    // the symmetric 128 x 256 tile has a single short phase per K-step and stalls at its barrier; a third B
+    // buffer was tried and changes nothing)
     make_instance<Shape<128, 128, 64, 256, 2, 4, 2, 2>, true>(0.47),
     make_instance<Shape<64, 128, 64, 256, 2, 4, 4, 2>, true>(0.88),
     make_instance<Shape<128, 128, 64, 128, 2, 2, 2, 2, -1, 0, 2, 2, 4>, true>(1.06),
