@@ -31,6 +31,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="square8192")
     ap.add_argument("--tiles", default="", help="T_MA,T_MC,T_K,T_N (default: the selector's pick)")
+    ap.add_argument("--shape", default="", help="M,N,K: the workload's input recipe at another size (for profiles of other shapes)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the per-instance sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--cpu-rows", type=int, default=1024, help="rows of C the oracle computes for the CPU baseline")
@@ -144,7 +145,10 @@ def main():
     atb.lib()                                         # fail loudly if the extension is missing
     cfg = workloads.CONFIGS[args.workload]
     M, N, K = cfg.M, cfg.N, cfg.K
-    A, Bb = workloads.make_inputs(cfg)
+    if args.shape:
+        M, N, K = (int(x) for x in args.shape.split(","))
+        args.workload = f"{args.workload}@{M}x{N}x{K}"
+    A, Bb = workloads.make_inputs(cfg, M=M, N=N, K=K)
     A_dev = torch.from_numpy(A).cuda()
     A_bfp = atb.bfp16_quantize(A_dev)
     # the quantiser is not part of the timed step (operands are quantised once); its own rate, for the record
