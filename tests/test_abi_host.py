@@ -147,7 +147,7 @@ def test_model_mi355x_mode_and_selector():
     assert all(ranked[i].pred_flops >= ranked[i + 1].pred_flops
                for i in range(len(ranked) - 1) if ranked[i + 1].feasible)
     small = atb.select_tiles(256, 256, 256)
-    assert small[0].T_MC == 64                        # 16 small tiles beat one big tile on 256 CUs
+    assert small[0].T_MC <= 64                        # many small tiles beat one big tile on 256 CUs
     assert atb.lib().atb_select_tiles(0, 1, 8, None, None, 0, None) == 1
 
 
