@@ -1187,6 +1187,10 @@ const Instance g_instances[] = {
     make_instance<Shape<128, 128, 64, 128, 2, 2, 2, 2, -1, 0, 2, 2, 4>, true>(1.06),
     make_instance<Shape<64, 128, 64, 128, 2, 2, 4, 2, -1, 0, 2, 2, 4>, true>(1.08),
     // small tiles for small problems
+    // 64 x 128 with T_K = 128 (one workgroup per CU): the instance for problems with about one such tile per CU
+    // (M = 1024, N = 2048: 546 - 676 TFLOP/s against 479 - 546 for the 64 x 64 tile); its ATB twin at T_MA = 32
+    // measured 522 - 601 there.  Factor: the one-round case; several rounds run at 0.62 - 0.75.
+    make_instance<Shape<64, 64, 128, 128, 2, 2, 2, 2, -1, 0, 2, 2, 4>, true>(0.83),
     make_instance<Shape<64, 64, 64, 64, 2, 2, 2, 2, -1, 0, 2, 2, 4>, true>(1.2),
     make_instance<Shape<32, 64, 64, 64, 1, 2, 2, 2, -1, 0, 2, 2, 2>, true>(1.24),
     // skinny problems (M <= 64 or so: one row of C tiles, fewer workgroups than CUs) are bound by the

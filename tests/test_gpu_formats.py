@@ -17,7 +17,8 @@ from helpers import bf16_tensor_bits, bits_to_bf16_tensor, pack_a_bfp, unpack_a_
 pytestmark = pytest.mark.gpu
 
 FMT_TILES = [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256),
-             (128, 128, 64, 256), (64, 128, 64, 256), (128, 128, 64, 128), (64, 128, 64, 128), (64, 64, 64, 64), (32, 64, 64, 64)]
+             (128, 128, 64, 256), (64, 128, 64, 256), (128, 128, 64, 128), (64, 128, 64, 128), (64, 64, 64, 64), (32, 64, 64, 64),
+             (64, 64, 128, 128)]
 COMBOS = [("bfp16", "bf16"), ("bf16", "bfp16"), ("bfp16", "bfp16")]
 
 

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 BIG = [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256), (32, 256, 64, 256)]
 WIDE_K = [(32, 256, 128, 256)]      # T_K = 128: feasible only with ATB
-SMALL = [(64, 64, 64, 64), (32, 64, 64, 64)]
+SMALL = [(64, 64, 64, 64), (32, 64, 64, 64), (64, 64, 128, 128)]
 MID = [(128, 128, 64, 256), (64, 128, 64, 256), (128, 128, 64, 128), (64, 128, 64, 128)]
 SKINNY = [(32, 64, 256, 64), (32, 32, 256, 64)]      # T_K = 256, a ring of 3 B buffers, helper waves: for problems with one or two rows of C tiles
 
