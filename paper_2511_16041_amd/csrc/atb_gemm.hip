@@ -1176,34 +1176,35 @@ const Instance g_instances[] = {
     // T_K = 128 exists only with ATB: at rho = 8 the A buffers take 17 KiB next to 128 KiB of B; the
     // symmetric tile would need 264 KiB of LDS (the "ATB makes an infeasible tile legal" case of Sec. 6.3)
     make_instance<Shape<32, 256, 128, 256, 1, 4, 8, 2>>(0.93),   // measured against the fit, which is dominated by the 2 x 4 grid instances
-    // mid-size tiles for problems with too few 256 x 256 tiles to fill 256 CUs (e.g. the N = 2048
-    // shapes of the paper's Table 3): 128 x 256 on 8 waves, 128 x 128 on 4 waves (two workgroups per CU)
-    // (the factors are measured full-load throughput over the 256 x 256 family's fit: workgroups that
-    // share a CU overlap each other's barriers and latencies, which the per-tile formula does not see;
-    // the symmetric 128 x 256 tile has a single short phase per K-step and stalls at its barrier; a third B
-    // buffer was tried and changes nothing)
+    // Mid-size tiles for problems with too few 256 x 256 tiles to fill 256 CUs (e.g. the N = 2048 shapes of the
+    // paper's Table 3).  Factors (first argument): measured full-load throughput over the 256 x 256 family's
+    // fit; workgroups that share a CU overlap each other's barriers and latencies, which the per-tile formula
+    // does not see.
+    // 128 x 256 on 8 waves, both wave groups multiply (as above).  The symmetric one has a single short phase per
+    // K-step and stalls at its barrier (a third B buffer and a deeper A fetch were tried and change nothing).
     make_instance<Shape<128, 128, 64, 256, 2, 4, 2, 2>, true>(0.47),
     make_instance<Shape<64, 128, 64, 256, 2, 4, 4, 2>, true>(0.88),
+    // 128 x 128 on a 2 x 2 grid of multiplying waves plus 4 helper waves that stage (last argument); two and
+    // three workgroups per CU.  Helper waves: 920 -> 1016 TFLOP/s at 8192^3, 343-369 -> 439-514 at M = 1024, N = 2048.
     make_instance<Shape<128, 128, 64, 128, 2, 2, 2, 2, -1, 0, 2, 2, 4>, true>(1.06),
     make_instance<Shape<64, 128, 64, 128, 2, 2, 4, 2, -1, 0, 2, 2, 4>, true>(1.08),
-    // small tiles for small problems
     // 64 x 128 with T_K = 128 (one workgroup per CU): the instance for problems with about one such tile per CU
     // (M = 1024, N = 2048: 546 - 676 TFLOP/s against 479 - 546 for the 64 x 64 tile); its ATB twin at T_MA = 32
     // measured 522 - 601 there.  Factor: the one-round case; several rounds run at 0.62 - 0.75.
     make_instance<Shape<64, 64, 128, 128, 2, 2, 2, 2, -1, 0, 2, 2, 4>, true>(0.83),
+    // Small tiles for small problems: four and six workgroups per CU, with 4 and 2 helper waves.
     make_instance<Shape<64, 64, 64, 64, 2, 2, 2, 2, -1, 0, 2, 2, 4>, true>(1.2),
     make_instance<Shape<32, 64, 64, 64, 1, 2, 2, 2, -1, 0, 2, 2, 2>, true>(1.24),
-    // skinny problems (M <= 64 or so: one row of C tiles, fewer workgroups than CUs) are bound by the
-    // latency of the B stream, not its bandwidth: a K-step of 256 keeps four times the bytes in flight
-    // (measured at M = 16 .. 128, N = K = 8192 before the helper waves: 43 - 57 us against 72 us for the 64-deep tiles; a symmetric
-    // 64 x 64 x 256 tile: 60 us; a ring of 3 B buffers instead of 2: no change, kept as the ATB instance's
-    // use of the LDS that its small A buffers leave)
-    // Its 1 x 2 wave grid would leave two SIMDs idle and issue decode, fragment reads and MFMAs in one
-    // in-order stream per wave: four helper waves take the staging instead (48 -> 38 us at M = 64; two
-    // helpers: 48 us, eight: 37 us).  Factor: measured 0.42 - 0.49 of the fit from M = 16 to 8192.
+    // Skinny problems (M <= 128 or so at large N, K: one or two rows of C tiles, fewer workgroups than CUs) are
+    // bound by what each workgroup keeps in flight and by how fast its few waves get through a K-step, not by
+    // bandwidth.  These two instances have K-steps of 256 (four times the bytes per round trip), a ring of three
+    // B buffers (NB; it fits because the ATB A buffers are small, and it is what lets the symmetric 32-row tile's
+    // single phase per K-step await its B tile two K-steps after the request), four helper waves next to the 1 x 2
+    // grid (which alone would leave two SIMDs idle), and take the dead-row-skipping variant of the kernel body.
+    // Measured at N = K = 8192 (64 x 64 x 64 tile: 72 us at every M <= 128): M <= 64: 27 - 29 us with the 32-row
+    // tile (4.7 - 5.0 TB/s of B), M = 128: 39 us with the 64-row tile.  Factors: 0.42 - 0.49 of the fit from
+    // M = 16 to 8192.
     make_instance<Shape<32, 64, 256, 64, 1, 2, 2, 2, -1, 0, 2, 3, 4>>(0.46),
-    // the same on a 32-row C tile (symmetric; the ring of 3 is what lets its single phase per K-step await the B
-    // tile two K-steps after the request): M <= 64 at N = K = 8192 in 27 - 29 us, 4.7 - 5.0 TB/s of B
     make_instance<Shape<32, 32, 256, 64, 1, 2, 2, 2, -1, 0, 2, 3, 4>>(0.46),
 };
 
