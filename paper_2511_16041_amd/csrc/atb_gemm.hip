@@ -133,6 +133,7 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 // [0, num_records) returns zero without touching memory, which is what masks the edges.
 struct Rsrc {
     __amdgpu_buffer_rsrc_t am, ae, b, bm, be;
+    intx4 b_words;      // the B descriptor once more as four dwords, for the hand-issued requests of the symmetric instances
 };
 
 constexpr int kRsrcFlags = 0x00020000;           // raw buffer, 32-bit data format
@@ -239,10 +240,11 @@ struct TileKernel {
     static constexpr int NPAIR_B = BTPT * 8;                                             // B mantissa pairs per thread per tile
     static constexpr int NSTEP_A = NPAIR == 0 ? 0 : SK ? NPAIR / 4 : NPAIR + 2;          // decode items per phase (A sub-tile): pipeline steps, or blocks
     static constexpr int NSTEP_B = NPAIR_B > 0 ? NPAIR_B / S::RHO + 2 : 0;               // ... and for this phase's share of the B tile
+    static constexpr bool ASM_DMA = VEC && !BBFP && S::RHO <= 2 && APT == 0 && BPT > 0;   // B requests issued by hand, see load_b_chunk
     static constexpr int APTN = APT > 0 ? APT : 1, BPTN = BPT > 0 ? BPT : 1, BTPTN = BTPT > 0 ? BTPT : 1;   // array extents
     static constexpr int B_BYTES = BBFP ? S::BT_BYTES : S::B_BYTES;
     static_assert(!BBFP || (NPAIR_B % S::RHO == 0 && S::T_K % 16 == 0 && (S::T_N * S::T_K / 16) % NTS == 0), "BFP16 B staging must split evenly");
-    static_assert(!BBFP || (S::LDS_BYTES_BT <= 160 * 1024 && S::NB == 2), "LDS budget of a gfx950 CU; the BFP16 B path has two buffers");
+    static_assert(!BBFP || S::LDS_BYTES_BT <= 160 * 1024, "LDS budget of a gfx950 CU (the BFP16 B path always has two buffers)");
     static_assert((ROLE == 0) == (S::CW != 8 && S::HW == 0) && (ROLE >= 3) == (S::HW > 0), "two staging groups exactly when two waves share a SIMD; helper roles exactly with helper waves");
 
     const GemmParams &p;
@@ -481,7 +483,16 @@ struct TileKernel {
     }
 
     // a K-step's offsets stay below 2^31, so a longer remainder may be cut off there
-    ATB_DEV void remake_b() { rs.b = make_rsrc(b_ptr, (int)min(b_left, (int64_t)0x7fffffff)); }
+    ATB_DEV void remake_b()
+    {
+        const int bytes = (int)min(b_left, (int64_t)0x7fffffff);
+        rs.b = make_rsrc(b_ptr, bytes);
+        if constexpr (ASM_DMA) {
+            const uint64_t a = reinterpret_cast<uint64_t>(b_ptr);
+            rs.b_words = intx4{__builtin_amdgcn_readfirstlane((int)(uint32_t)a), __builtin_amdgcn_readfirstlane((int)(uint32_t)(a >> 32) & 0xFFFF),
+                               __builtin_amdgcn_readfirstlane(bytes), kRsrcFlags};
+        }
+    }
 
     ATB_DEV void remake_bt()
     {
@@ -566,7 +577,22 @@ struct TileKernel {
 #if defined(__HIP_DEVICE_COMPILE__)
             typedef __attribute__((address_space(3))) void lds_void;
             char *dst = (S::NB > 2) ? b_req[0] + b_fill_off : b_req[buf];
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rs.b, (lds_void *)(dst + i * (NTS * 16)), 16, b_off[i], 0, 0, 0);
+            if constexpr (ASM_DMA) {
+                // Issued by hand so that the compiler does not know of it: it cannot tell the buffer being
+                // filled from the one being read and puts a vmcnt(0) in front of every transposing fragment
+                // read that follows a request it knows of -- a full memory round trip inside the K-step when
+                // requests and fragment reads share a phase, as they do at rho = 1 (measured: the symmetric
+                // 128 x 256 tile 522 -> 992 TFLOP/s).  Completion is awaited by wait_vm() before the publishing
+                // barrier, as for the built-in form.  Requests the compiler does not count make its own vmcnt
+                // waits stricter, which is harmless only for waves that request nothing else: waves that also
+                // fetch A would await the B tile before every decode (measured: helper waves 10 - 20 % slower),
+                // so only wave groups without A requests take this path.
+                const unsigned lds_addr = (unsigned)reinterpret_cast<uintptr_t>(dst + i * (NTS * 16));
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                             :: "s"(__builtin_amdgcn_readfirstlane((int)lds_addr)), "v"(b_off[i]), "s"(rs.b_words) : "memory");
+            } else {
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs.b, (lds_void *)(dst + i * (NTS * 16)), 16, b_off[i], 0, 0, 0);
+            }
 #else
             (void)buf;   // the host pass only parses this function
 #endif
@@ -1180,10 +1206,12 @@ const Instance g_instances[] = {
     // paper's Table 3).  Factors (first argument): measured full-load throughput over the 256 x 256 family's
     // fit; workgroups that share a CU overlap each other's barriers and latencies, which the per-tile formula
     // does not see.
-    // 128 x 256 on 8 waves, both wave groups multiply (as above).  The symmetric one has a single short phase per
-    // K-step and stalls at its barrier (a third B buffer and a deeper A fetch were tried and change nothing).
-    make_instance<Shape<128, 128, 64, 256, 2, 4, 2, 2>, true>(0.47),
-    make_instance<Shape<64, 128, 64, 256, 2, 4, 4, 2>, true>(0.88),
+    // 128 x 256 on 8 waves, both wave groups multiply (as above); the B requests are issued by hand (see
+    // load_b_chunk: 522 -> 1010 TFLOP/s symmetric, 977 -> 1063 at rho = 2, on 8192^3), and the symmetric one,
+    // whose single short phase per K-step leaves a B tile little time to arrive, has a ring of three B buffers
+    // (1010 -> 1042).
+    make_instance<Shape<128, 128, 64, 256, 2, 4, 2, 2, -1, 0, 2, 3>, true>(0.94),
+    make_instance<Shape<64, 128, 64, 256, 2, 4, 4, 2>, true>(0.96),
     // 128 x 128 on a 2 x 2 grid of multiplying waves plus 4 helper waves that stage (last argument); two and
     // three workgroups per CU.  Helper waves: 920 -> 1016 TFLOP/s at 8192^3, 343-369 -> 439-514 at M = 1024, N = 2048.
     make_instance<Shape<128, 128, 64, 128, 2, 2, 2, 2, -1, 0, 2, 2, 4>, true>(1.06),
