@@ -1189,13 +1189,14 @@ const Instance g_instances[] = {
     // T_MC = T_N = 256, T_K = 64: the sweep over rho = 1, 2, 4, 8.
     // 8 waves (2 x 4, two per SIMD, 128 accumulator registers each) let one wave's decode and memory
     // instructions issue while the other's MFMAs run; T_MA = 32 only feeds a 1 x 4 grid.
-    // Staging split (last two arguments): the first wave group decodes all of A and the second
-    // requests all of B, except at rho = 1, where a quarter of the (large) A tile goes to the second
-    // group as well (measured on 8192^3: 1195 against 1164 TFLOP/s for the even split and 950 for 4 : 0).
+    // Staging split (last two arguments): the first wave group decodes all of A and the second requests
+    // all of B, by hand (see load_b_chunk) at rho <= 2.  (While the symmetric tile's B requests were the
+    // built-in ones, a quarter of its A tile went to the second group: 1195 TFLOP/s against 950 for this
+    // 4 : 0 split; with hand-issued requests 4 : 0 measures 1294 against 1243 for 3 : 1, on 8192^3.)
     // The A fetch runs one to one and a half K-steps ahead of its use at every rho (PF phases).
     // These three, and the mid-size and small tiles below, also come with B and/or C stored as BFP16
     // (the all-BFP16 configurations of Sec. 6.1); the 4-wave 256-row instances have no registers left for it.
-    make_instance<Shape<256, 256, 64, 256, 2, 4, 2, 2, 3, 0>, true>(),
+    make_instance<Shape<256, 256, 64, 256, 2, 4, 2, 2, 4, 0>, true>(),
     make_instance<Shape<128, 256, 64, 256, 2, 4, 2, 2, 2, 0>, true>(),
     make_instance<Shape<64, 256, 64, 256, 2, 4, 4, 2, 1, 0>, true>(),
     make_instance<Shape<32, 256, 64, 256, 1, 4, 8, 4>>(),

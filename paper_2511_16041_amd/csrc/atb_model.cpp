@@ -93,14 +93,14 @@ extern "C" void atb_hw_params_mi355x(atb_hw_params *hw)
     hw->buffer_bytes = 160.0 * 1024.0;           // LDS per CU
     hw->acc_bytes = 256.0 * 1024.0;              // 4 waves x 256 accumulator VGPRs x 64 lanes x 4 B
     // Least-squares fit to the measured K-step times of the 256x256x64 instances at rho = 1, 2, 4, 8
-    // on 8192^3 (in cycles of the nominal 2.4 GHz clock): 3747 + 124 rho + 274 / rho, against 2048
-    // cycles of MFMA issue, i.e. Eff_micro(64) = 0.547.  T_K = 128 measured no better than 64, so the
+    // on 8192^3 (in cycles of the nominal 2.4 GHz clock): 3792 + 138 rho + 197 / rho, against 2048
+    // cycles of MFMA issue, i.e. Eff_micro(64) = 0.540.  T_K = 128 measured no better than 64, so the
     // fit saturates early (small eps): Eff_micro ~ 1 / II.
-    hw->delta_cycles = 124.0;
-    hw->fill_cycles = 274.0;
+    hw->delta_cycles = 138.0;
+    hw->fill_cycles = 197.0;
     hw->eta = 1.0;
     hw->eps = 0.4;
-    hw->II = 1.8235;
+    hw->II = 1.8453;
     hw->a_bytes = 1.125;                         // A BFP16: 9 bytes per 8 elements
     hw->b_bytes = 2.0;
     hw->c_bytes = 2.0;
