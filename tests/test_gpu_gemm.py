@@ -240,3 +240,23 @@ def test_skinny_shapes(tiles, shape):
     mant, expo = oracle.quantize(A)
     C_ref, T, _ = oracle.gemm(mant, expo, Bb)
     _check(_run(mant, expo, Bb, tiles), C_ref, T, f"skinny {shape} {tiles}")
+
+
+def test_every_instance_gives_the_same_bits():
+    """Tiling changes data movement, not arithmetic: every instance adds the products of an output element in the
+    same order (k ascending, 16 per MFMA, one fp32 accumulator), so on any data all instances must agree bit for
+    bit -- whatever rho, T_K, wave grid, helper waves or staging variant."""
+    shape = (520, 516, 328)
+    M, N, K = shape
+    print(f"gemm invariance {shape}", flush=True)
+    A, Bb = workloads.make_inputs(workloads.CONFIGS["ragged"], M=M, N=N, K=K)
+    mant, expo = oracle.quantize(A)
+    first = None
+    for tiles in atb.instances():
+        got = _run(mant, expo, Bb, tiles)
+        if first is None:
+            first = got
+            C_ref, T, _ = oracle.gemm(mant, expo, Bb)
+            _check(got, C_ref, T, f"invariance {tiles}")
+        else:
+            assert np.array_equal(got, first), f"{tiles} differs from {atb.instances()[0]} in {np.count_nonzero(got != first)} elements"
