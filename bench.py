@@ -34,7 +34,7 @@ def parse_args():
     ap.add_argument("--shape", default="", help="M,N,K: the workload's input recipe at another size (for profiles of other shapes)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the per-instance sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--cpu-rows", type=int, default=1024, help="rows of C the oracle computes for the CPU baseline")
+    ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of C the oracle computes for the CPU baseline")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run a plain device-to-device copy of known size instead (reference for the HBM byte counters)")
     return ap.parse_args()
