@@ -11,7 +11,10 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libatb.so")
 OBJ_DIR = os.path.join(HERE, "_build")
-SOURCES = ["atb_gemm.hip", "atb_bfp16.hip", "atb_model.cpp", "atb_api.cpp"]
+# (source, object name, extra flags): the GEMM instance table is cut into three groups that compile side by side
+SOURCES = [("atb_gemm.hip", "atb_gemm_g0", ["-DATB_GROUP=0"]), ("atb_gemm.hip", "atb_gemm_g1", ["-DATB_GROUP=1"]),
+           ("atb_gemm.hip", "atb_gemm_g2", ["-DATB_GROUP=2"]), ("atb_bfp16.hip", "atb_bfp16", []),
+           ("atb_model.cpp", "atb_model", []), ("atb_api.cpp", "atb_api", [])]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
@@ -24,10 +27,11 @@ COMMON = [
 ]
 
 
-def _compile(src: str, extra, verbose: bool) -> str:
-    obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
+def _compile(item, extra, verbose: bool) -> str:
+    src, name, flags = item
+    obj = os.path.join(OBJ_DIR, name + ".o")
     lang = ["-x", "hip"]
-    cmd = [HIPCC] + COMMON + list(extra) + lang + ["-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC] + COMMON + list(flags) + list(extra) + lang + ["-c", os.path.join(CSRC, src), "-o", obj]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
@@ -36,7 +40,7 @@ def _compile(src: str, extra, verbose: bool) -> str:
 
 def build(verbose: bool = False, extra=()) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(lambda s: _compile(s, extra, verbose), SOURCES))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", OUT] + objs
     if verbose:

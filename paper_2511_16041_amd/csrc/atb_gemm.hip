@@ -33,6 +33,7 @@
 // holds one row m (= l % 32) and 16 columns n = 8*(v/4) + 4*(l/32) + v%4,
 // i.e. groups of 4 consecutive columns -> 8-byte bf16 stores.
 #include <algorithm>
+#include <vector>
 
 #include "atb_internal.h"
 
@@ -1185,7 +1186,15 @@ Instance make_instance(double eff_scale = 1.0, double lone_cap = 0.0)
     return i;
 }
 
+// The instance table is cut into three groups so that the build can compile them side by side (one
+// translation unit per group, -DATB_GROUP=0/1/2); without the macro this file holds all of them.
+#ifndef ATB_GROUP
+#define ATB_GROUP -1
+#endif
+#define ATB_IN_GROUP(g) (ATB_GROUP == -1 || ATB_GROUP == (g))
+
 const Instance g_instances[] = {
+#if ATB_IN_GROUP(0)
     // T_MC = T_N = 256, T_K = 64: the sweep over rho = 1, 2, 4, 8.
     // 8 waves (2 x 4, two per SIMD, 128 accumulator registers each) let one wave's decode and memory
     // instructions issue while the other's MFMAs run; T_MA = 32 only feeds a 1 x 4 grid.
@@ -1203,6 +1212,8 @@ const Instance g_instances[] = {
     // T_K = 128 exists only with ATB: at rho = 8 the A buffers take 17 KiB next to 128 KiB of B; the
     // symmetric tile would need 264 KiB of LDS (the "ATB makes an infeasible tile legal" case of Sec. 6.3)
     make_instance<Shape<32, 256, 128, 256, 1, 4, 8, 2>>(0.93),   // measured against the fit, which is dominated by the 2 x 4 grid instances
+#endif
+#if ATB_IN_GROUP(1)
     // Mid-size tiles for problems with too few 256 x 256 tiles to fill 256 CUs (e.g. the N = 2048 shapes of the
     // paper's Table 3).  Factors (first argument): measured full-load throughput over the 256 x 256 family's
     // fit; workgroups that share a CU overlap each other's barriers and latencies, which the per-tile formula
@@ -1217,6 +1228,8 @@ const Instance g_instances[] = {
     // three workgroups per CU.  Helper waves: 920 -> 1016 TFLOP/s at 8192^3, 343-369 -> 439-514 at M = 1024, N = 2048.
     make_instance<Shape<128, 128, 64, 128, 2, 2, 2, 2, -1, 0, 2, 2, 4>, true>(1.06),
     make_instance<Shape<64, 128, 64, 128, 2, 2, 4, 2, -1, 0, 2, 2, 4>, true>(1.08),
+#endif
+#if ATB_IN_GROUP(2)
     // 64 x 128 with T_K = 128 (one workgroup per CU): the instance for problems with about one such tile per CU
     // (M = 1024, N = 2048: 546 - 676 TFLOP/s against 479 - 546 for the 64 x 64 tile); its ATB twin at T_MA = 32
     // measured 522 - 601 there.  Factor: the one-round case; several rounds run at 0.62 - 0.75.
@@ -1235,20 +1248,57 @@ const Instance g_instances[] = {
     // M = 16 to 8192.
     make_instance<Shape<32, 64, 256, 64, 1, 2, 2, 2, -1, 0, 2, 3, 4>>(0.46),
     make_instance<Shape<32, 32, 256, 64, 1, 2, 2, 2, -1, 0, 2, 3, 4>>(0.46),
+#endif
 };
-
 
 }  // namespace
 
+#if ATB_GROUP == -1
 int instance_count() { return (int)(sizeof(g_instances) / sizeof(g_instances[0])); }
 const Instance &instance(int i) { return g_instances[i]; }
+#else
+#define ATB_CAT2(a, b) a##b
+#define ATB_CAT(a, b) ATB_CAT2(a, b)
+// this group's slice of the table
+const Instance *ATB_CAT(instances_group, ATB_GROUP)(int *n)
+{
+    *n = (int)(sizeof(g_instances) / sizeof(g_instances[0]));
+    return g_instances;
+}
+#if ATB_GROUP == 0
+const Instance *instances_group1(int *n);
+const Instance *instances_group2(int *n);
+namespace {
+const std::vector<Instance> &all_instances()
+{
+    static const std::vector<Instance> table = [] {
+        std::vector<Instance> t;
+        int n = 0;
+        const Instance *g = instances_group0(&n);
+        t.insert(t.end(), g, g + n);
+        g = instances_group1(&n);
+        t.insert(t.end(), g, g + n);
+        g = instances_group2(&n);
+        t.insert(t.end(), g, g + n);
+        return t;
+    }();
+    return table;
+}
+}  // namespace
+int instance_count() { return (int)all_instances().size(); }
+const Instance &instance(int i) { return all_instances()[i]; }
+#endif
+#endif
+
+#if ATB_GROUP == -1 || ATB_GROUP == 0
 int find_instance(int T_MA, int T_MC, int T_K, int T_N)
 {
     for (int i = 0; i < instance_count(); ++i) {
-        const Instance &x = g_instances[i];
+        const Instance &x = instance(i);
         if (x.T_MA == T_MA && x.T_MC == T_MC && x.T_K == T_K && x.T_N == T_N) return i;
     }
     return -1;
 }
+#endif
 
 }  // namespace atb
