@@ -1246,7 +1246,7 @@ const Instance g_instances[] = {
     // Measured at N = K = 8192 (64 x 64 x 64 tile: 72 us at every M <= 128): M <= 64: 27 - 29 us with the 32-row
     // tile (4.7 - 5.0 TB/s of B), M = 128: 39 us with the 64-row tile.  Factors: 0.42 - 0.49 of the fit from
     // M = 16 to 8192.
-    make_instance<Shape<32, 64, 256, 64, 1, 2, 2, 2, -1, 0, 2, 3, 4>>(0.46),
+    make_instance<Shape<32, 64, 256, 64, 1, 2, 2, 2, -1, 0, 2, 3, 4>>(0.50),
     make_instance<Shape<32, 32, 256, 64, 1, 2, 2, 2, -1, 0, 2, 3, 4>>(0.46),
 #endif
 };
