@@ -255,3 +255,22 @@ def test_create_rejects_sizes_beyond_32_bit_offsets():
     assert create(64, 1 << 23, 64, (32, 256, 128, 256)) == 1  # 2 N (T_K + 1) >= 2^31 with T_K = 128
     assert create(64, 1 << 23, 64, (128, 256, 64, 256)) == 0
     L.atb_gemm_destroy(h)
+
+
+def test_selector_against_measured_sweep():
+    """The selector's pick against a measured sweep of every instance over 20 problem shapes (large squares, the
+    N = 2048 shapes of the paper's Table 3, skinny problems): within 5 % of the fastest instance on each, and the
+    predicted throughput of the pick within 30 % of its measurement (20 % but for M = 16)."""
+    import os
+    inst = atb.instances()
+    rows = [l.split() for l in open(os.path.join(os.path.dirname(__file__), "golden", "mi355x_shape_sweep.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 20
+    for f in rows:
+        M, N, K = (int(x) for x in f[:3])
+        meas = [float(x) for x in f[3:]]
+        assert len(meas) == len(inst)
+        pick = atb.select_tiles(M, N, K)[0]
+        got = meas[inst.index(pick.tiles())]
+        assert got >= 0.95 * max(meas), ((M, N, K), pick.tiles(), got, inst[meas.index(max(meas))], max(meas))
+        assert abs(pick.pred_flops / 1e12 / got - 1) < (0.30 if M < 32 else 0.20), ((M, N, K), pick.tiles(), pick.pred_flops / 1e12, got)
