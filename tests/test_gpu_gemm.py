@@ -260,3 +260,25 @@ def test_every_instance_gives_the_same_bits():
             _check(got, C_ref, T, f"invariance {tiles}")
         else:
             assert np.array_equal(got, first), f"{tiles} differs from {atb.instances()[0]} in {np.count_nonzero(got != first)} elements"
+
+
+def test_random_shapes_every_instance():
+    """Twenty seeded random shapes (M, N <= 700, K <= 1024 in steps of 8, N even and odd) through every instance:
+    all instances must agree with each other bit for bit and with the oracle within the tolerance."""
+    rng = np.random.default_rng(2024)
+    for case in range(20):
+        M = int(rng.integers(1, 701))
+        N = int(rng.integers(1, 701))
+        K = 8 * int(rng.integers(1, 129))
+        print(f"gemm random shape {case}: {(M, N, K)}", flush=True)
+        A, Bb = workloads.make_inputs(workloads.CONFIGS["ragged"], M=M, N=N, K=K)
+        mant, expo = oracle.quantize(A)
+        C_ref, T, _ = oracle.gemm(mant, expo, Bb)
+        first = None
+        for tiles in atb.instances():
+            got = _run(mant, expo, Bb, tiles)
+            if first is None:
+                first = got
+                _check(got, C_ref, T, f"random {(M, N, K)} {tiles}")
+            else:
+                assert np.array_equal(got, first), f"{(M, N, K)}: {tiles} differs from {atb.instances()[0]}"
