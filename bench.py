@@ -7,7 +7,16 @@ One "step" is one pass of the whole hot path over one synthetic problem: a
 single atb_gemm_run (tile decomposition, B-tile fetch, A sub-tile fetch, BFP16
 decode, MFMA microkernels, sub-tile switches, epilogue).  Inputs (A already
 quantised to BFP16 by atb_bfp16_quantize, B bf16) are resident in HBM before
-the timed region.  Prints ONE JSON line.
+the timed region.  Prints ONE JSON line; exits with status 1 if an output that
+was checked against the CPU oracle lies outside the tolerance.
+
+Beside the headline (value, roofline, cpu_baseline) the line carries: the five
+workloads with the selector's pick and its symmetric / ATB siblings
+("configs"), the sweep over every instance on the headline workload
+("rho_sweep"), shapes that none of the selector's constants were fitted on
+("held_out_shapes"), the MFMA-only ceiling measured in the same process
+("mfma_probe"), the other storage formats, the problem sizes of the paper's
+Table 3, per-launch spread and a cold-cache figure, the quantiser's rate.
 """
 from __future__ import annotations
 
@@ -22,6 +31,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+# problem shapes that no constant of the selector or of the microkernel model was fitted on
+HELD_OUT_SHAPES = [(6144, 6144, 3072), (1536, 7168, 4096), (384, 4096, 4096), (2560, 2560, 5120)]
 
 
 def parse_args():
@@ -32,8 +43,8 @@ def parse_args():
     ap.add_argument("--workload", default="square8192")
     ap.add_argument("--tiles", default="", help="T_MA,T_MC,T_K,T_N (default: the selector's pick)")
     ap.add_argument("--shape", default="", help="M,N,K: the workload's input recipe at another size (for profiles of other shapes)")
-    ap.add_argument("--no-sweep", action="store_true", help="skip the per-instance sweep")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-sweep", action="store_true", help="headline only: skip the sweeps, the other workloads and the probe")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle (baseline and output checks)")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of C the oracle computes for the CPU baseline")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run a plain device-to-device copy of known size instead (reference for the HBM byte counters)")
@@ -55,21 +66,23 @@ def copy_probe():
     print(json.dumps({"copy_probe": True, "bytes_read_per_copy": n, "bytes_written_per_copy": n, "copies": 10}), flush=True)
 
 
+def _ranks(x):
+    order = sorted(range(len(x)), key=lambda i: x[i])
+    r = [0.0] * len(x)
+    i = 0
+    while i < len(order):
+        j = i
+        while j + 1 < len(order) and x[order[j + 1]] == x[order[i]]:
+            j += 1
+        for k in range(i, j + 1):
+            r[order[k]] = (i + j) / 2.0
+        i = j + 1
+    return r
+
+
 def spearman(a, b):
-    """Rank correlation of two equally long sequences (no tie correction needed at this size)."""
-    def ranks(x):
-        order = sorted(range(len(x)), key=lambda i: x[i])
-        r = [0.0] * len(x)
-        i = 0
-        while i < len(order):
-            j = i
-            while j + 1 < len(order) and x[order[j + 1]] == x[order[i]]:
-                j += 1
-            for k in range(i, j + 1):
-                r[order[k]] = (i + j) / 2.0
-            i = j + 1
-        return r
-    ra, rb = ranks(a), ranks(b)
+    """Rank correlation of two equally long sequences."""
+    ra, rb = _ranks(a), _ranks(b)
     n = len(a)
     ma, mb = sum(ra) / n, sum(rb) / n
     cov = sum((x - ma) * (y - mb) for x, y in zip(ra, rb))
@@ -78,18 +91,29 @@ def spearman(a, b):
     return cov / (va * vb) if va > 0 and vb > 0 else 0.0
 
 
+def kendall(a, b):
+    """Kendall's tau-a of two equally long sequences."""
+    n, s = len(a), 0
+    for i in range(n):
+        for j in range(i + 1, n):
+            d = (a[i] - a[j]) * (b[i] - b[j])
+            s += (d > 0) - (d < 0)
+    return 2.0 * s / (n * (n - 1)) if n > 1 else 0.0
+
+
 def hbm_traffic(workload, tiles):
-    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one for this
-    workload and these tile factors (the counters cannot be read from inside this process)."""
+    """HBM bytes per launch of this workload with these tile factors, from the committed rocprofv3 counter
+    summary (counters cannot be read from inside this process): (bytes or None, where the figure comes from)."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    src = "profiles/hbm_traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this command; not measured in this run)"
     if not os.path.exists(path):
-        return None
+        return None, src
     try:
         table = json.load(open(path))
     except Exception:
-        return None
+        return None, src
     key = f"{workload}:{','.join(str(t) for t in tiles)}"
-    return table.get(key, {}).get("bytes_per_launch")
+    return table.get(key, {}).get("bytes_per_launch"), src
 
 
 def time_plan(plan, A_bfp, B, C, steps, warmup):
@@ -110,6 +134,17 @@ def time_plan(plan, A_bfp, B, C, steps, warmup):
     return wall, ev0.elapsed_time(ev1) / steps
 
 
+def burn_in(plan, A_bfp, B, C, seconds=0.06):
+    """The shader clock needs some tens of milliseconds of load to settle after an idle pause (host-side input
+    generation is one): run the same launch for a while, untimed."""
+    import torch
+    t = time.perf_counter()
+    while time.perf_counter() - t < seconds:
+        for _ in range(10):
+            plan.run(A_bfp, B, C)
+        torch.cuda.synchronize()
+
+
 def time_per_launch(plan, sets, launches):
     """`launches` launches, each between its own pair of events on the launch stream (no host sync in
     between), cycling through the operand sets `sets` = [(A_bfp, B, C), ...].  Returns the list of ms."""
@@ -124,6 +159,39 @@ def time_per_launch(plan, sets, launches):
         evs[i + 1].record()
     torch.cuda.synchronize()
     return [evs[i].elapsed_time(evs[i + 1]) for i in range(launches)]
+
+
+def time_tiles(atb, M, N, K, tiles, A_bfp, B, C, steps, warmup):
+    """Mean kernel ms of one instance on resident operands."""
+    p = atb.Gemm(M, N, K, *tiles)
+    _, kms = time_plan(p, A_bfp, B, C, steps, warmup)
+    p.close()
+    return kms
+
+
+def entry(tiles, flop, kms, model_tflops=None):
+    t = flop / (kms * 1e-3) / 1e12
+    e = {"tiles": list(tiles), "rho": tiles[1] // tiles[0], "tflops": round(t, 1), "frac_of_bf16_peak": round(t / PEAK_BF16_TFLOPS, 4)}
+    if model_tflops is not None:
+        e["model_tflops"] = round(model_tflops, 1)
+    return e
+
+
+def check_rows(np, torch, oracle, atb, raw_a, Bb, C, M, N, K, rows):
+    """Rows `rows` of the device result C against the oracle: (max error / tolerance, rows checked)."""
+    mant, expo, _ = atb.bfp16_unpack_host(raw_a, M, K)
+    C_ref, T, _ = oracle.gemm(mant, expo, Bb, rows=rows)
+    got = oracle.bf16_to_double(C[torch.from_numpy(rows).to(C.device)].cpu().view(torch.int16).numpy().view(np.uint16))
+    err = np.abs(got - oracle.bf16_to_double(C_ref))
+    return float(np.max(err / oracle.tolerance(T))), int(len(rows))
+
+
+def band_sample(np, M, n, seed=1):
+    """Up to n rows: the edges plus random rows out of distinct 32-row bands."""
+    rng = np.random.default_rng(seed)
+    bands = rng.permutation((M + 31) // 32)[:n]
+    rows = [min(M - 1, int(b) * 32 + int(rng.integers(0, 32))) for b in bands] + [0, M - 1]
+    return np.array(sorted(set(rows)), dtype=np.int64)
 
 
 def main():
@@ -143,6 +211,9 @@ def main():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
         sys.exit(1)
     atb.lib()                                         # fail loudly if the extension is missing
+    oracle = None
+    if not args.no_cpu:
+        import oracle                                 # the cpu_baseline leg: baseline timing and the output checks that reuse its rows
     cfg = workloads.CONFIGS[args.workload]
     M, N, K = cfg.M, cfg.N, cfg.K
     if args.shape:
@@ -161,7 +232,7 @@ def main():
     qe1.record()
     torch.cuda.synchronize()
     quant_ms = qe0.elapsed_time(qe1) / 10
-    del A_dev
+    del A_dev, A
     B = torch.from_numpy(Bb.view(np.int16)).view(torch.bfloat16).cuda()
     C = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
     torch.cuda.synchronize()
@@ -172,21 +243,17 @@ def main():
     else:
         tiles = ranked[0].tiles()
     flop = 2.0 * M * N * K
+    parity_worst = 0.0
 
     raw_a = A_bfp.cpu().numpy() if not args.no_cpu else None
     plan = atb.Gemm(M, N, K, *tiles)
     info = plan.launch_info()
-    # The shader clock needs some tens of milliseconds of load to settle after an idle pause (the host-side input
-    # generation above is one): whatever --warmup says, the GPU first runs the same launch for ~60 ms, untimed.
-    t_burn = time.perf_counter()
-    while time.perf_counter() - t_burn < 0.06:
-        for _ in range(10):
-            plan.run(A_bfp, B, C)
-        torch.cuda.synchronize()
+    burn_in(plan, A_bfp, B, C)
     wall, kernel_ms = time_plan(plan, A_bfp, B, C, args.steps, args.warmup)
     ms_per_step = wall / args.steps * 1e3
     tflops = flop / (wall / args.steps) / 1e12
     kernel_tflops = flop / (kernel_ms * 1e-3) / 1e12
+    C_timed = C.clone()                               # the timed plan's output, checked against the oracle below
     # per-launch spread with resident operands, and one figure with cold caches: the operand sets rotate, and
     # the bytes touched between two uses of a set exceed the 256 MiB memory-side cache (and the 32 MiB of L2)
     per = sorted(time_per_launch(plan, [(A_bfp, B, C)], 50))
@@ -201,23 +268,7 @@ def main():
                              "tflops": round(flop / (cold[len(cold) // 2] * 1e-3) / 1e12, 1)}}
     plan.close()
 
-    sweep = []
-    if not args.no_sweep:
-        pred = {c.tiles(): c.pred_flops / 1e12 for c in ranked}
-        for t in atb.instances():
-            if t[1] != tiles[1] and (M * N) // (t[1] * t[3]) > 65536:
-                continue
-            p = atb.Gemm(M, N, K, *t)
-            _, kms = time_plan(p, A_bfp, B, C, max(5, args.steps // 2), 5)
-            p.close()
-            sweep.append({"tiles": list(t), "rho": t[1] // t[0], "tflops": round(flop / (kms * 1e-3) / 1e12, 1),
-                          "model_tflops": round(pred.get(t, 0.0), 1)})
-        sym = [s for s in sweep if s["rho"] == 1 and s["tiles"][1:] == list(tiles[1:])]
-        best_atb = max([s for s in sweep if s["rho"] > 1 and s["tiles"][1:] == list(tiles[1:])],
-                       key=lambda s: s["tflops"], default=None)
-    else:
-        sym, best_atb = [], None
-
+    traffic, traffic_src = hbm_traffic(args.workload, tiles)
     out = {
         "metric": "TFLOPS (BFP16xBF16 GEMM, 8192^3) + % of bf16 MFMA peak; ATB vs symmetric speedup",
         "value": round(tflops, 2),
@@ -239,7 +290,7 @@ def main():
         "pct_of_bf16_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": {"bound": "mfma", "achieved": round(kernel_tflops, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(kernel_tflops / PEAK_BF16_TFLOPS, 4),
-                     "traffic": hbm_traffic(args.workload, tiles),
+                     "traffic": traffic, "traffic_source": traffic_src,
                      "kernel": "atb_gemm_kernel", "kernel_ms": round(kernel_ms, 4),
                      "algorithmic_flop_per_launch": flop},
     }
@@ -248,14 +299,64 @@ def main():
                         "achieved": round(5.125 * M * K / (quant_ms * 1e-3) / 1e9, 1), "peak": 8000.0, "unit": "GB/s",
                         "frac": round(5.125 * M * K / (quant_ms * 1e-3) / 8e12, 4),
                         "algorithmic_bytes": "4 read + 1.125 written per element of A"}
-    if sweep:
+
+    if not args.no_sweep:
+        # What the matrix pipes sustain with nothing else going on: an MFMA-only loop on register operands, one
+        # workgroup of 8 waves per CU, pseudo-random bf16 operands (and constant ones: less power, higher clock).
+        # clock_mhz_from_mfma_rate: the loop's MFMAs follow each other back to back, 32 cycles each per SIMD, so the
+        # shader clock under that load is at least (MFMAs per SIMD * 32) / time; the kernel's two clock counters beside it.
+        sink = torch.empty(256 * 512, dtype=torch.float32, device="cuda")
+        clk = torch.zeros(2, dtype=torch.int64, device="cuda")
+        probe = {}
+        for name, rnd in (("random_bf16", True), ("constant", False)):
+            iters = 800
+            for _ in range(60):
+                atb.mfma_probe(sink, clk, 256, iters, rnd)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                pflop = atb.mfma_probe(sink, clk, 256, iters, rnd)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 20
+            ticks = clk.cpu().numpy()
+            probe[name] = {"tflops": round(pflop / (ms * 1e-3) / 1e12, 1), "kernel_ms": round(ms, 4),
+                           "clock_mhz_from_mfma_rate": round(2 * iters * 32 * 32 / (ms * 1e-3) / 1e6, 0),
+                           "s_memtime_ticks": int(ticks[0]), "s_memrealtime_ticks_100mhz": int(ticks[1])}
+        out["mfma_probe"] = probe
+        meas_peak = probe["random_bf16"]["tflops"]
+        out["pct_of_measured_mfma_peak"] = round(100.0 * kernel_tflops / meas_peak, 2)
+        out["roofline"]["measured_mfma_only_peak"] = meas_peak
+        out["roofline"]["frac_of_measured_peak"] = round(kernel_tflops / meas_peak, 4)
+        del sink, clk
+
+    sweep = []
+    if not args.no_sweep:
+        pred = {c.tiles(): c.pred_flops / 1e12 for c in ranked}
+        for t in atb.instances():
+            if t[1] != tiles[1] and (M * N) // (t[1] * t[3]) > 65536:
+                continue
+            kms = time_tiles(atb, M, N, K, t, A_bfp, B, C, max(5, args.steps // 2), 5)
+            sweep.append(entry(t, flop, kms, pred.get(t, 0.0)))
+        sym = [s for s in sweep if s["rho"] == 1 and s["tiles"][1:] == list(tiles[1:])]
+        best_atb = max([s for s in sweep if s["rho"] > 1 and s["tiles"][1:] == list(tiles[1:])],
+                       key=lambda s: s["tflops"], default=None)
         out["rho_sweep"] = sweep
         if sym and best_atb:
             out["atb_vs_symmetric"] = round(best_atb["tflops"] / sym[0]["tflops"], 4)
+            out["atb_vs_symmetric_by_family"] = {}
+            for fam in sorted({tuple(s["tiles"][1:]) for s in sweep}):
+                s1 = [s for s in sweep if tuple(s["tiles"][1:]) == fam and s["rho"] == 1]
+                sa = [s for s in sweep if tuple(s["tiles"][1:]) == fam and s["rho"] > 1]
+                if s1 and sa:
+                    out["atb_vs_symmetric_by_family"]["x".join(str(v) for v in fam)] = round(max(s["tflops"] for s in sa) / s1[0]["tflops"], 4)
         fam = [s for s in sweep if s["tiles"][1:] == list(tiles[1:])]
         if len(fam) >= 3:
-            out["model_vs_measured_rank_spearman"] = round(spearman([s["model_tflops"] for s in fam],
-                                                                    [s["tflops"] for s in fam]), 3)
+            # in-sample: the selector's delta / fill / II constants are a fit to this very family on this workload
+            out["model_vs_measured_rank"] = {"scope": "in-sample (the model's constants were fitted to this family on this workload)",
+                                             "spearman": round(spearman([s["model_tflops"] for s in fam], [s["tflops"] for s in fam]), 3),
+                                             "kendall_tau": round(kendall([s["model_tflops"] for s in fam], [s["tflops"] for s in fam]), 3)}
 
     if not args.no_sweep and (N % 8) == 0 and tiles in ((256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256)):
         # the other storage formats of the same tile (B handed over as B^T in BFP16, C written as BFP16)
@@ -270,9 +371,109 @@ def main():
         del Bt_bfp
         out["storage_formats"] = fmts
 
+    # CPU baseline: the oracle on the first rows of the headline problem, and the timed output against those rows
+    if not args.no_cpu:
+        nrows = min(args.cpu_rows, M)
+        mant, expo, _ = atb.bfp16_unpack_host(raw_a, M, K)
+        t0 = time.perf_counter()
+        C_ref, T, threads = oracle.gemm(mant[:nrows].copy(), expo[:nrows].copy(), Bb)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(2.0 * nrows * N * K / dt / 1e12, 5), "unit": "TFLOP/s",
+                               "cores": int(threads), "kind": "oracle",
+                               "sample": f"first {nrows} of {M} rows of C (all {N} columns, full K={K}), "
+                                         f"{dt:.1f} s; fp64 accumulate"}
+        got = oracle.bf16_to_double(C_timed[:nrows].cpu().view(torch.int16).numpy().view(np.uint16))
+        err = np.abs(got - oracle.bf16_to_double(C_ref))
+        worst = float(np.max(err / oracle.tolerance(T)))
+        out["parity"] = {"headline_rows_checked": int(nrows), "headline_max_err_over_tol": round(worst, 4)}
+        parity_worst = max(parity_worst, worst)
+        del mant, expo, C_ref, T, got, err
+    del C_timed
+
     if not args.no_sweep and args.workload == "square8192":
-        # the problem sizes of the paper's Table 3 (N = 2048), each with the selector's pick
         del A_bfp, B, C
+        # ---- the five workloads: the selector's pick, the symmetric tile and its ATB siblings, each checked
+        # against the oracle on sampled rows (one random row out of up to 64 distinct 32-row bands, plus the edges)
+        configs = []
+        for name in ("small256", "square4096", "square8192", "mlp", "ragged"):
+            c = workloads.CONFIGS[name]
+            Ax, Bx = workloads.make_inputs(c)
+            Mx, Kx = Ax.shape
+            Nx = Bx.shape[1]
+            Ab = atb.bfp16_quantize(torch.from_numpy(Ax).cuda())
+            del Ax
+            Bd = torch.from_numpy(Bx.view(np.int16)).view(torch.bfloat16).cuda()
+            Cd = torch.empty((Mx, Nx), dtype=torch.bfloat16, device="cuda")
+            fl = 2.0 * Mx * Nx * Kx
+            rk = atb.select_tiles(Mx, Nx, Kx)
+            prd = {r.tiles(): r.pred_flops / 1e12 for r in rk}
+            pick = rk[0].tiles()
+            if name == "small256":
+                fam = [(32, 64, 64, 64), (64, 64, 64, 64)]               # the workload names T_MA = 32, T_MC = 64
+            else:
+                fam = [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256)]
+                if name == "square8192":
+                    fam.append((32, 256, 64, 256))
+            todo = [pick] + [t for t in fam if t != pick]
+            small = fl < 1e10
+            p0 = atb.Gemm(Mx, Nx, Kx, *pick)
+            burn_in(p0, Ab, Bd, Cd)
+            p0.close()
+            ents = []
+            for t in todo:
+                kms = time_tiles(atb, Mx, Nx, Kx, t, Ab, Bd, Cd, 200 if small else 30, 300 if small else 10)
+                e = entry(t, fl, kms, prd.get(t))
+                e["role"] = ("selector pick, " if t == pick else "") + ("symmetric" if t[0] == t[1] else "ATB")
+                ents.append(e)
+            rec = {"workload": name, "M": Mx, "N": Nx, "K": Kx, "instances": ents}
+            sy = [e for e in ents if e["rho"] == 1]
+            at = [e for e in ents if e["rho"] > 1]
+            if sy and at:
+                rec["atb_vs_symmetric"] = round(max(e["tflops"] for e in at) / sy[0]["tflops"], 4)
+            if not args.no_cpu:
+                Cd.fill_(float("nan"))
+                p0 = atb.Gemm(Mx, Nx, Kx, *pick)
+                p0.run(Ab, Bd, Cd)
+                torch.cuda.synchronize()
+                p0.close()
+                rows = band_sample(np, Mx, 64)
+                worst, n = check_rows(np, torch, oracle, atb, Ab.cpu().numpy(), Bx, Cd, Mx, Nx, Kx, rows)
+                rec["max_err_over_tol"] = round(worst, 4)
+                rec["rows_checked"] = n
+                parity_worst = max(parity_worst, worst if worst == worst else float("inf"))
+            configs.append(rec)
+            del Ab, Bd, Cd, Bx
+        out["configs"] = configs
+
+        # ---- shapes the selector has never seen: every instance timed, the pick against the best,
+        # predicted against measured throughput, rank agreement over all instances
+        held = []
+        for (Mx, Nx, Kx) in HELD_OUT_SHAPES:
+            Ax, Bx = workloads.make_inputs(cfg, M=Mx, N=Nx, K=Kx)
+            Ab = atb.bfp16_quantize(torch.from_numpy(Ax).cuda())
+            del Ax
+            Bd = torch.from_numpy(Bx.view(np.int16)).view(torch.bfloat16).cuda()
+            Cd = torch.empty((Mx, Nx), dtype=torch.bfloat16, device="cuda")
+            fl = 2.0 * Mx * Nx * Kx
+            rk = atb.select_tiles(Mx, Nx, Kx)
+            prd = {r.tiles(): r.pred_flops / 1e12 for r in rk}
+            inst = atb.instances()
+            p0 = atb.Gemm(Mx, Nx, Kx, *rk[0].tiles())
+            burn_in(p0, Ab, Bd, Cd)
+            p0.close()
+            meas = {t: fl / (time_tiles(atb, Mx, Nx, Kx, t, Ab, Bd, Cd, 30, 15) * 1e-3) / 1e12 for t in inst}
+            best = max(meas, key=meas.get)
+            pick = rk[0].tiles()
+            held.append({"M": Mx, "N": Nx, "K": Kx, "pick": list(pick), "pick_tflops": round(meas[pick], 1),
+                         "pick_model_tflops": round(prd[pick], 1), "best": list(best), "best_tflops": round(meas[best], 1),
+                         "pick_vs_best": round(meas[pick] / meas[best], 4),
+                         "spearman": round(spearman([prd[t] for t in inst], [meas[t] for t in inst]), 3),
+                         "kendall_tau": round(kendall([prd[t] for t in inst], [meas[t] for t in inst]), 3)})
+            del Ab, Bd, Cd
+        out["held_out_shapes"] = {"scope": "out-of-sample: no constant of the selector was fitted on these shapes",
+                                  "instances_timed": len(atb.instances()), "shapes": held}
+
+        # ---- the problem sizes of the paper's Table 3 (N = 2048), each with the selector's pick
         scaling = []
         for Mx in (1024, 2048, 4096):
             for Kx in (2048, 4096, 8192):
@@ -293,20 +494,13 @@ def main():
         out["table3_shapes"] = scaling
 
     if not args.no_cpu:
-        import oracle
-        lay = atb.bfp16_layout(M, K)
-        raw = raw_a
-        nrows = min(args.cpu_rows, M)
-        mant, expo, _ = atb.bfp16_unpack_host(raw, M, K)
-        mant, expo = mant[:nrows].copy(), expo[:nrows].copy()
-        t0 = time.perf_counter()
-        _, _, threads = oracle.gemm(mant, expo, Bb)
-        dt = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": round(2.0 * nrows * N * K / dt / 1e12, 5), "unit": "TFLOP/s",
-                               "cores": int(threads), "kind": "oracle",
-                               "sample": f"first {nrows} of {M} rows of C (all {N} columns, full K={K}), "
-                                         f"{dt:.1f} s; fp64 accumulate"}
+        out["parity"]["worst_err_over_tol"] = round(parity_worst, 4)
+        out["parity"]["ok"] = bool(parity_worst <= 1.0)
     print(json.dumps(out), flush=True)
+    if not args.no_cpu and not parity_worst <= 1.0:
+        print(f"bench.py: an output checked against the oracle is outside the tolerance (worst error / tolerance = {parity_worst})",
+              file=sys.stderr)
+        sys.exit(1)
 
 
 if __name__ == "__main__":

@@ -267,6 +267,27 @@ atb_status atb_model_microkernel(int T_MA, int T_MC, int T_K, int T_N, int wave_
 /* Wave grid and residency of compiled instance `index` (inputs of the call above). */
 atb_status atb_instance_geometry(int index, int *wave_m, int *wave_n, int *wg_per_cu);
 
+/* ------------------------------------------------------- measurement aid */
+
+/* An MFMA-only loop on register operands (no memory traffic, no LDS), for
+ * benches that quote the GEMM against what the matrix pipes of this chip
+ * sustain in practice as well as against the nominal peak (the nominal figure
+ * assumes a clock the chip does not hold under full matrix load).  Not a step
+ * of the GEMM.
+ * Launches `workgroups` workgroups of 8 waves (two per SIMD, as the GEMM's
+ * large tiles); each wave issues iters * 32 v_mfma_f32_32x32x16_bf16 on
+ * operands that rotate over four register sets; random_operands != 0 fills
+ * them with pseudo-random bf16 (random sign and mantissa, exponents 2^-7 .. 2),
+ * 0 with the constant 1.0 (which draws less power, hence a higher clock).
+ * sink_dev: DEVICE, at least workgroups * 512 * 4 bytes, overwritten (keeps the
+ * arithmetic alive).  clocks_dev: DEVICE or NULL; two uint64 written by the
+ * first wave: the kernel's length in ticks of the shader-clock counter
+ * (s_memtime) and of the constant 100 MHz counter (s_memrealtime).
+ * *flop (HOST, may be NULL) receives the floating-point operations of the
+ * launch.  Async on hip_stream; workgroups in [1, 65536], iters in [1, 2^20]. */
+atb_status atb_mfma_probe(void *sink_dev, void *clocks_dev, int workgroups, int iters,
+                          int random_operands, void *hip_stream, double *flop);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,9 +24,9 @@ def build(verbose: bool = False) -> str:
 
 
 def ensure_built() -> str:
-    # Build only when nothing is built: after editing the source, run this
-    # file (or __graft_entry__.build()) again.
-    if not os.path.exists(OUT):
+    """Path of the shared object; builds it first if it is missing or older than its source."""
+    if not os.path.exists(OUT) or os.path.getmtime(SRC) > os.path.getmtime(OUT) or \
+            os.path.getmtime(os.path.abspath(__file__)) > os.path.getmtime(OUT):
         build()
     return OUT
 

@@ -10,6 +10,17 @@ per element of A, B and C.  Where the paper is inconsistent (it quotes 1.25 B
 per BFP16 element in Sec. 3.1 and 9 B per 8 elements in Sec. 2.4) the caller
 chooses; tests/test_oracle_model.py shows which value reproduces which column
 of Table 2.
+
+What pins what (tests/test_oracle_model.py): Sec. 3 formulas <- Table 2's
+columns; Eq. (4) <- the worked example of Sec. 4.1 and brute force over all
+issue orders; Eqs. (5), (7), (8), (9) <- a cycle-by-cycle list scheduler (exact
+for a single chain, lower bounds otherwise, as the paper states them);
+cluster_loads <- the 8 -> 4 example of Sec. 4.2; the chain efficiency of Sec. 5,
+Eq. (12) and eff_micro_ilp <- Table 1's Eff_micro column; Eqs. (14), (15) <-
+Table 1's trends.  Parity unpinned: Eq. (6) for C > 1 (as printed it falls
+below one cycle per VMAC once C > P, the paper prints no value of it, and
+Table 1 is met with the one-per-cycle floor binding) and Eq. (10) (checked
+only against Eq. (9) algebraically).
 """
 from __future__ import annotations
 
@@ -106,6 +117,52 @@ def eff_micro_chain(N_accum, C, T_prolog, II, T_epilog) -> float:
     """Sec. 5, un-numbered: N_accum / (T_prolog + II (N_accum - C) + T_epilog)
     (the N_clusters factor cancels)."""
     return N_accum / (T_prolog + II * (N_accum - C) + T_epilog)
+
+
+def cluster_loads(rows: int, cols: int, shared: bool) -> int:
+    """Sec. 4.2, "Sharing Input Across Chain Cluster": operand loads per
+    k-slice of a rows x cols cluster of accumulation chains.  Unshared, each
+    of the rows*cols VMACs loads its own A and its own B operand; shared, one
+    A operand per cluster row and one B operand per cluster column feed all
+    of them."""
+    return rows + cols if shared else 2 * rows * cols
+
+
+# Microbenchmarked parameters of the bfp16ebs8 VMAC that Sec. 4.3 states.
+XDNA2_VMAC = {
+    "k_per_vmac": 8,       # 8x8x8 MAC unit (Sec. 2.4)
+    "n_acc_regs": 5,       # accumulator registers of 8x8 fp32
+    "P": 3,                # VMAC pipeline distance
+    "l_load": 8,           # operand load latency
+    "U_LD": 2,             # vector load units (Sec. 4)
+    "l_vmac_vst": 6,
+    "l_store": 2,
+    "n_store": 2,          # store instructions per accumulator register
+}
+
+
+def eff_micro_ilp(T_K: int, rows: int = 2, cols: int = 2, hw=None) -> float:
+    """Microkernel efficiency from the instruction-level model, composed in
+    the paper's order: prolog = Eq. (4) over the cluster's operand loads,
+    II = Eq. (6), steady state = Eq. (7), epilog = Eq. (8), one cluster after
+    another = Eq. (9), efficiency = VMACs issued / cycles (Sec. 4, Sec. 5).
+
+    Readings (the paper leaves them open): the cluster is rows x cols chains
+    with shared inputs (Sec. 4.2; 2 x 2 is the example it draws, and the
+    largest square cluster that five accumulator registers hold); N_accum
+    counts the VMACs of the whole cluster, C * T_K / 8; R_load is the
+    cluster's loads per k-slice; and II is floored at one cycle per VMAC,
+    because Sec. 4.1 gives every instruction a throughput of one per cycle and
+    there is one vector arithmetic unit (Eq. (6) as printed falls below one
+    for C > P)."""
+    hw = XDNA2_VMAC if hw is None else hw
+    C = rows * cols
+    loads = cluster_loads(rows, cols, shared=True)
+    N_accum = C * (T_K // hw["k_per_vmac"])
+    T_prolog = t_load([hw["l_load"]], [loads], hw["U_LD"])
+    II = max(1.0, ii_parallel(hw["P"], loads, hw["U_LD"], C))
+    T_epi = t_epilog(hw["l_vmac_vst"], hw["l_store"], hw["n_store"], C)
+    return eff_micro_chain(N_accum, C, T_prolog, II, T_epi)
 
 
 def eff_micro(T_K: float, eta: float, eps: float, II: float) -> float:

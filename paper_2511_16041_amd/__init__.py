@@ -66,7 +66,7 @@ EXPORTS = [
     "atb_status_string", "atb_last_hip_error", "atb_gemm_create", "atb_gemm_create_fmt", "atb_gemm_run", "atb_gemm_destroy",
     "atb_gemm_launch_info", "atb_instance_count", "atb_instance_get", "atb_bfp16_layout", "atb_bfp16_bytes",
     "atb_bfp16_quantize", "atb_bfp16_decode", "atb_hw_params_xdna2", "atb_hw_params_mi355x",
-    "atb_model_eval", "atb_select_tiles", "atb_model_microkernel", "atb_instance_geometry",
+    "atb_model_eval", "atb_select_tiles", "atb_model_microkernel", "atb_instance_geometry", "atb_mfma_probe",
 ]
 
 
@@ -115,6 +115,8 @@ def lib() -> ctypes.CDLL:
     L.atb_model_microkernel.argtypes = [ci, ci, ci, ci, ci, ci, ci, ctypes.POINTER(MicroModel)]
     L.atb_instance_geometry.restype = ci
     L.atb_instance_geometry.argtypes = [ci, pi, pi, pi]
+    L.atb_mfma_probe.restype = ci
+    L.atb_mfma_probe.argtypes = [vp, vp, ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
     _lib = L
     return L
 
@@ -243,6 +245,19 @@ def bfp16_decode(A_bfp, M: int, K: int, stream=None):
     _check(lib().atb_bfp16_decode(ctypes.c_void_p(A_bfp.data_ptr()), ctypes.c_void_p(out.data_ptr()), M, K,
                                   _stream_ptr(stream)), "atb_bfp16_decode")
     return out
+
+
+def mfma_probe(sink, clocks, workgroups: int, iters: int, random_operands: bool = True, stream=None) -> float:
+    """Launch the MFMA-only measurement loop (atb_mfma_probe).  sink: CUDA float32 tensor of at least
+    workgroups * 512 elements; clocks: CUDA int64 tensor of 2 elements, or None.  Returns the launch's flop."""
+    import torch
+    assert sink.is_cuda and sink.dtype == torch.float32 and sink.numel() >= workgroups * 512
+    assert clocks is None or (clocks.is_cuda and clocks.dtype == torch.int64 and clocks.numel() >= 2)
+    flop = ctypes.c_double()
+    _check(lib().atb_mfma_probe(ctypes.c_void_p(sink.data_ptr()), ctypes.c_void_p(clocks.data_ptr()) if clocks is not None else None,
+                                workgroups, iters, 1 if random_operands else 0, _stream_ptr(stream), ctypes.byref(flop)),
+           "atb_mfma_probe")
+    return flop.value
 
 
 @dataclass

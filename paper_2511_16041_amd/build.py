@@ -13,7 +13,7 @@ OUT = os.path.join(HERE, "libatb.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 # (source, object name, extra flags): the GEMM instance table is cut into three groups that compile side by side
 SOURCES = [("atb_gemm.hip", "atb_gemm_g0", ["-DATB_GROUP=0"]), ("atb_gemm.hip", "atb_gemm_g1", ["-DATB_GROUP=1"]),
-           ("atb_gemm.hip", "atb_gemm_g2", ["-DATB_GROUP=2"]), ("atb_bfp16.hip", "atb_bfp16", []),
+           ("atb_gemm.hip", "atb_gemm_g2", ["-DATB_GROUP=2"]), ("atb_bfp16.hip", "atb_bfp16", []), ("atb_probe.hip", "atb_probe", []),
            ("atb_model.cpp", "atb_model", []), ("atb_api.cpp", "atb_api", [])]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -62,14 +62,26 @@ def build_microbench(verbose: bool = False) -> str:
     return exe
 
 
-def ensure_built() -> str:
-    # Build only when nothing is built; after editing a source, run this file again.
+def _stale() -> bool:
+    """True if the library is missing or older than any of its sources (or this file)."""
     if not os.path.exists(OUT):
+        return True
+    built = os.path.getmtime(OUT)
+    deps = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if os.path.isfile(os.path.join(CSRC, f))]
+    deps += [os.path.join(ROOT, "include", "atb.h"), os.path.abspath(__file__)]
+    return any(os.path.getmtime(d) > built for d in deps)
+
+
+def ensure_built() -> str:
+    """Path of the library; builds it first if it is missing or a source is newer than it.  (A stale
+    library that cannot be rebuilt because there is no compiler is an error, not a silent fallback.)"""
+    if _stale():
         build()
     return OUT
 
 
 if __name__ == "__main__":
-    extra = [a for a in sys.argv[1:]]
+    extra = [a for a in sys.argv[1:] if a != "--microbench"]
     print(build(verbose=True, extra=extra))
-    print(build_microbench(verbose=True))
+    if "--microbench" in sys.argv:
+        print(build_microbench(verbose=True))

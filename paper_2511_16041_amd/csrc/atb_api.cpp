@@ -1,5 +1,6 @@
 // C ABI of libatb (see include/atb.h): argument checking, plans, launches.
 #include <algorithm>
+#include <cstdio>
 #include <cstdlib>
 #include <new>
 
@@ -157,6 +158,14 @@ extern "C" atb_status atb_gemm_create_fmt(atb_gemm **out, int64_t M, int64_t N, 
     // so that the result can be the BFP16 operand of a following GEMM as it is
     if (c_format == ATB_FMT_BFP16) p.tiles_n = (int)((atb::round_up(N, atb::kPanelK) + T_N - 1) / T_N);
     p.group_m = (int)std::max<int64_t>(1, 2048 / T_MC);   // an XCD's patch of C tiles is 2048 rows high
+    if (const char *log = std::getenv("ATB_LOG"); log && log[0] == '1') {
+        const atb::Instance &x = atb::instance(idx);
+        std::fprintf(stderr, "atb_gemm_create: M=%lld N=%lld K=%lld T_MA=%d T_MC=%d T_K=%d T_N=%d rho=%d b=%s c=%s "
+                             "instance=%d waves=%dx%d threads=%d lds=%d tiles=%dx%d group_m=%d k_panels=%d\n",
+                     (long long)M, (long long)N, (long long)K, T_MA, T_MC, T_K, T_N, T_MC / T_MA,
+                     b_format == ATB_FMT_BFP16 ? "bfp16" : "bf16", c_format == ATB_FMT_BFP16 ? "bfp16" : "bf16", idx,
+                     x.wave_m, x.wave_n, x.threads, x.lds_bytes, p.tiles_m, p.tiles_n, p.group_m, p.k_panels);
+    }
     *out = g;
     return ATB_OK;
 }
@@ -197,4 +206,14 @@ extern "C" atb_status atb_gemm_launch_info(const atb_gemm *g, int64_t *workgroup
     if (threads) *threads = x.threads;
     if (lds_bytes) *lds_bytes = x.lds_bytes;
     return ATB_OK;
+}
+
+extern "C" atb_status atb_mfma_probe(void *sink, void *clocks, int workgroups, int iters, int random_operands,
+                                     void *stream, double *flop)
+{
+    if (!sink || workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 20)) return ATB_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(sink) & 3u) != 0 || (reinterpret_cast<uintptr_t>(clocks) & 7u) != 0) return ATB_ERR_INVALID_ARG;
+    if (flop) *flop = atb::mfma_probe_flop(workgroups, iters);
+    return hip_status(atb::launch_mfma_probe(static_cast<float *>(sink), static_cast<unsigned long long *>(clocks), workgroups,
+                                             iters, random_operands != 0, static_cast<hipStream_t>(stream)));
 }

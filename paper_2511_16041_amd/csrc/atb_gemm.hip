@@ -33,7 +33,7 @@
 // holds one row m (= l % 32) and 16 columns n = 8*(v/4) + 4*(l/32) + v%4,
 // i.e. groups of 4 consecutive columns -> 8-byte bf16 stores.
 #include <algorithm>
-#include <vector>
+#include <mutex>
 
 #include "atb_internal.h"
 
@@ -141,32 +141,6 @@ constexpr int kRsrcFlags = 0x00020000;           // raw buffer, 32-bit data form
 
 #define ATB_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-// Per-wave time stamps for kernel tuning (s_memtime at the start of a microkernel, at its end and
-// after the switch barrier, summed per wave of workgroup 0); compiled out of the library: ATB_TRACE
-// is defined only by a developer's timing harness, which reads atb_trace_acc back.
-#ifdef ATB_TRACE
-__device__ unsigned long long atb_trace_acc[16 * 8];
-#define ATB_TRACE_DECL unsigned long long trace_prev = 0, trace_sum[8] = {}
-#define ATB_STAMP(id)                                                              \
-    do {                                                                           \
-        if (blockIdx.x == 0) {                                                     \
-            unsigned long long now = __builtin_amdgcn_s_memtime();                 \
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");                     \
-            trace_sum[id] += now - trace_prev;                                     \
-            trace_prev = now;                                                      \
-        }                                                                          \
-    } while (0)
-#define ATB_TRACE_FLUSH()                                                          \
-    do {                                                                           \
-        if (blockIdx.x == 0 && threadIdx.x % 64 == 0 && threadIdx.x / 64 < 16)      \
-            for (int i = 0; i < 8; ++i) atb_trace_acc[(threadIdx.x / 64) * 8 + i] = trace_sum[i]; \
-    } while (0)
-#else
-#define ATB_TRACE_DECL
-#define ATB_STAMP(id) do { } while (0)
-#define ATB_TRACE_FLUSH() do { } while (0)
-#endif
-
 // Origin of the t-th tile of this workgroup's XCD (false past the end of the walk).  Workgroups
 // are dealt round-robin to the 8 XCDs (each with its own L2); XCD x owns the contiguous run of
 // tiles [x * per_xcd, (x + 1) * per_xcd), walked in bands of group_m tile rows so that the
@@ -242,6 +216,9 @@ struct TileKernel {
     static constexpr int NSTEP_A = NPAIR == 0 ? 0 : SK ? NPAIR / 4 : NPAIR + 2;          // decode items per phase (A sub-tile): pipeline steps, or blocks
     static constexpr int NSTEP_B = NPAIR_B > 0 ? NPAIR_B / S::RHO + 2 : 0;               // ... and for this phase's share of the B tile
     static constexpr bool ASM_DMA = VEC && !BBFP && S::RHO <= 2 && APT == 0 && BPT > 0;   // B requests issued by hand, see load_b_chunk
+    // a wave group that issues requests by hand issues no other loads: the compiler's own vmcnt waits (for loads it
+    // knows of) would otherwise count the hand-issued requests as well, and its built-in LDS-direct loads use M0 too
+    static_assert(!ASM_DMA || (APT == 0 && BTPT == 0 && VEC && !BBFP), "hand-issued B requests only in wave groups without compiler-visible loads");
     static constexpr int APTN = APT > 0 ? APT : 1, BPTN = BPT > 0 ? BPT : 1, BTPTN = BTPT > 0 ? BTPT : 1;   // array extents
     static constexpr int B_BYTES = BBFP ? S::BT_BYTES : S::B_BYTES;
     static_assert(!BBFP || (NPAIR_B % S::RHO == 0 && S::T_K % 16 == 0 && (S::T_N * S::T_K / 16) % NTS == 0), "BFP16 B staging must split evenly");
@@ -294,7 +271,6 @@ struct TileKernel {
     unsigned dec[4];                   // bf16 pairs of the BFP16 block being decoded
     float cvf[2][2], ldf[2][2];        // decode pipeline: converted and scaled pairs in flight
     int shift;
-    ATB_TRACE_DECL;
 
     ATB_DEV TileKernel(const GemmParams &p_, char *lds, int t_first, int t_stride_) : p(p_), t_stride(t_stride_)
     {
@@ -589,8 +565,12 @@ struct TileKernel {
                 // fetch A would await the B tile before every decode (measured: helper waves 10 - 20 % slower),
                 // so only wave groups without A requests take this path.
                 const unsigned lds_addr = (unsigned)reinterpret_cast<uintptr_t>(dst + i * (NTS * 16));
-                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                             :: "s"(__builtin_amdgcn_readfirstlane((int)lds_addr)), "v"(b_off[i]), "s"(rs.b_words) : "memory");
+                // M0 (the LDS base of the request) is put back afterwards: the compiler reserves it for its own uses
+                // and is not told about this one
+                int m0_saved;
+                asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, 0 offen lds\n\ts_mov_b32 m0, %0"
+                             : "=&s"(m0_saved)
+                             : "s"(__builtin_amdgcn_readfirstlane((int)lds_addr)), "v"(b_off[i]), "s"(rs.b_words) : "memory");
             } else {
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs.b, (lds_void *)(dst + i * (NTS * 16)), 16, b_off[i], 0, 0, 0);
             }
@@ -878,9 +858,7 @@ struct TileKernel {
             constexpr int g = ki * S::RHO + s;
             if constexpr (S::AB == 2 && COMPUTE) read_first_band<(g * S::PER) % 2>(a_rd[g % 2]);
             ATB_FENCE();
-            ATB_STAMP(1);
             slots<ki, s, 0>();
-            ATB_STAMP(2);
             // The B tile requested (straight into LDS) in the first phase of a K-step is read in the
             // last band of the next K-step, so the last barrier before that band has to publish it.
             // With NB buffers the tile read in K-step kt + 1 was requested at the start of K-step kt + 2 - NB.
@@ -892,7 +870,6 @@ struct TileKernel {
             if constexpr (VEC && BPT > 0 && S::RHO >= 2 && s == S::RHO - 2)
                 wait_vm<vm_cap((S::NB * S::RHO - 1) * A_VMEM + (S::NB - 1) * BPT)>();
             switch_barrier();   // the "kernel switch" of the ATB nest
-            ATB_STAMP(3);
             phases<ki, s + 1>();
         }
     }
@@ -970,7 +947,6 @@ struct TileKernel {
         // >= K, which read as zero.  The last K-steps of a tile already request, decode and stage the
         // first operands of the workgroup's next tile (the request streams have moved on to it), so the
         // next tile needs no prologue: the epilogue is all that separates two tiles' arithmetic.
-        ATB_STAMP(0);
         for (;;) {
             for (int kt = 0; kt < kt_steps; kt += S::KU) ksteps<0>();
             if constexpr (!COMPUTE) { } else if constexpr (CBFP) store_c_bfp(); else store_c();
@@ -983,7 +959,6 @@ struct TileKernel {
 #pragma unroll
                     for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
         }
-        ATB_TRACE_FLUSH();
         // the requests past the end of the walk (they read zeros) target registers and LDS of this wave
         wait_vm<0>();
     }
@@ -1113,21 +1088,23 @@ __global__ void __launch_bounds__(S::NT) atb_gemm_kernel(const GemmParams p)
     }
 }
 
-// Workgroups of this kernel that one CU holds at a time (LDS- or register-limited), times the CUs.
-template <class S, bool VEC, bool BBFP, bool CBFP>
-int resident_workgroups()
+// Compute units of the current device (0 if there is none).  Looked up once per device; the table is
+// guarded, so concurrent first launches from several threads are fine, and the lookup enqueues nothing
+// (a first launch inside a stream capture is as good as any other).
+inline int compute_units()
 {
-    static int cached = 0;
-    if (cached == 0) {
-        int dev = 0, cus = 0, per_cu = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, atb_gemm_kernel<S, VEC, BBFP, CBFP>, S::NT, 0) != hipSuccess ||
-            cus < 8 || per_cu < 1)
-            return 0;
-        cached = cus * per_cu;
+    constexpr int kMaxDevices = 64;
+    static std::mutex guard;
+    static int cached[kMaxDevices] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+    std::lock_guard<std::mutex> lock(guard);
+    if (cached[dev] == 0) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 8) return 0;
+        cached[dev] = cus;
     }
-    return cached;
+    return cached[dev];
 }
 
 template <class S, bool VEC, bool BBFP, bool CBFP>
@@ -1135,12 +1112,19 @@ hipError_t launch_kernel(const GemmParams &p, hipStream_t stream)
 {
     const int total = p.tiles_m * p.tiles_n;
     const int per_xcd = (total + 7) / 8;
-    const int resident = resident_workgroups<S, VEC, BBFP, CBFP>();
-    if (resident == 0) return hipErrorInvalidDevice;
     // Small tiles keep one workgroup per tile: several of them share a CU and overlap each other's
     // prologue and epilogue already, and the hardware dispatcher balances them better than a fixed walk.
+    // The 256 x 256 tiles get a persistent grid of one workgroup per CU (their LDS footprint admits no
+    // second one): a grid larger than what is resident would only queue, a smaller one idles CUs.
     constexpr bool persistent = S::T_MC * S::T_N >= 256 * 256;
-    const int slots = persistent ? std::min(per_xcd, resident / 8) : per_xcd;     // workgroups per XCD
+    constexpr int lds = BBFP ? S::LDS_BYTES_BT : S::LDS_BYTES;
+    static_assert(!persistent || 2 * lds > 160 * 1024, "the persistent grid assumes one workgroup per CU");
+    int slots = per_xcd;                                                           // workgroups per XCD
+    if (persistent) {
+        const int cus = compute_units();
+        if (cus == 0) return hipErrorNoDevice;
+        slots = std::min(per_xcd, cus / 8);
+    }
     hipLaunchKernelGGL((atb_gemm_kernel<S, VEC, BBFP, CBFP>), dim3(slots * 8), dim3(S::NT), 0, stream, p);
     return hipGetLastError();
 }
@@ -1270,24 +1254,34 @@ const Instance *ATB_CAT(instances_group, ATB_GROUP)(int *n)
 const Instance *instances_group1(int *n);
 const Instance *instances_group2(int *n);
 namespace {
-const std::vector<Instance> &all_instances()
-{
-    static const std::vector<Instance> table = [] {
-        std::vector<Instance> t;
+// the three groups' slices side by side, gathered once (no allocation: nothing here can throw)
+struct InstanceTable {
+    static constexpr int kMax = 32;
+    Instance items[kMax];
+    int count = 0;
+    void append(const Instance *g, int n)
+    {
+        for (int i = 0; i < n && count < kMax; ++i) items[count++] = g[i];
+    }
+    InstanceTable()
+    {
         int n = 0;
         const Instance *g = instances_group0(&n);
-        t.insert(t.end(), g, g + n);
+        append(g, n);
         g = instances_group1(&n);
-        t.insert(t.end(), g, g + n);
+        append(g, n);
         g = instances_group2(&n);
-        t.insert(t.end(), g, g + n);
-        return t;
-    }();
+        append(g, n);
+    }
+};
+const InstanceTable &all_instances()
+{
+    static const InstanceTable table;
     return table;
 }
 }  // namespace
-int instance_count() { return (int)all_instances().size(); }
-const Instance &instance(int i) { return all_instances()[i]; }
+int instance_count() { return all_instances().count; }
+const Instance &instance(int i) { return all_instances().items[i]; }
 #endif
 #endif
 

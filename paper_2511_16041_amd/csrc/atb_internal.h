@@ -49,6 +49,10 @@ hipError_t launch_quantize(const float *A, int64_t lda, int8_t *Am, uint8_t *Ae,
                            hipStream_t stream);
 hipError_t launch_decode(const int8_t *Am, const uint8_t *Ae, uint16_t *out, int64_t M, int64_t K,
                          hipStream_t stream);
+// MFMA-only measurement loop (atb_probe.hip)
+hipError_t launch_mfma_probe(float *sink, unsigned long long *clocks, int workgroups, int iters, int random, hipStream_t stream);
+double mfma_probe_flop(int workgroups, int iters);
+size_t mfma_probe_sink_bytes(int workgroups);
 constexpr int kPanelK = 64;      // K extent of a panel of the BFP16 layout
 
 static inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }

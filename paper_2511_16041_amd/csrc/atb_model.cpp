@@ -163,6 +163,7 @@ extern "C" atb_status atb_select_tiles(int64_t M, int64_t N, int64_t K, const at
                                        atb_choice *ranked, int capacity, int *count)
 {
     if (M < 1 || N < 1 || K < 1 || capacity < 0 || (capacity > 0 && !ranked)) return ATB_ERR_INVALID_ARG;
+    try {
     std::vector<atb_choice> all;
     for (int i = 0; i < atb::instance_count(); ++i) {
         const atb::Instance &x = atb::instance(i);
@@ -199,6 +200,9 @@ extern "C" atb_status atb_select_tiles(int64_t M, int64_t N, int64_t K, const at
     if (count) *count = (int)all.size();
     for (int i = 0; i < capacity && i < (int)all.size(); ++i) ranked[i] = all[i];
     return ATB_OK;
+    } catch (...) {
+        return ATB_ERR_NOMEM;       // the ranking's scratch vector is the only thing here that can throw
+    }
 }
 
 extern "C" atb_status atb_model_microkernel(int T_MA, int T_MC, int T_K, int T_N, int wave_m, int wave_n,

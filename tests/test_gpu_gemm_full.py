@@ -1,5 +1,8 @@
-"""Full-size workloads in the launch configuration bench.py times: sampled rows of C against the
-oracle (the oracle computes whole rows one by one), plus the exactness property at full size."""
+"""Full-size workloads in the launch configuration bench.py times: the whole of C against the oracle
+(every element, within the tolerance), every compiled instance against the first bit for bit, plus the
+exactness property at full size."""
+import time
+
 import numpy as np
 import pytest
 
@@ -10,22 +13,29 @@ from helpers import bf16_tensor_bits, bits_to_bf16_tensor, unpack_a_bfp
 
 pytestmark = pytest.mark.gpu
 
+# workload -> instances whose whole C is compared with the oracle element by element
 CASES = [
     ("square4096", [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256)]),
     ("square8192", [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256), (32, 256, 64, 256), (32, 256, 128, 256)]),
     ("mlp", [(256, 256, 64, 256), (64, 256, 64, 256)]),
     ("ragged", [(256, 256, 64, 256), (64, 256, 64, 256), (32, 64, 64, 64), (32, 256, 128, 256)]),
 ]
+ORACLE_CHUNK = 1024      # rows of C the oracle computes per call (bounds the fp64 temporaries)
 
 
-def _sample_rows(M, rng, n=40):
+def _band_rows(M, rng):
+    """Edge rows of the first and last tiles plus one random row out of every 32-row band (the unit a
+    wave owns), so that no band of any tile row goes unchecked."""
     edge = [0, 1, 31, 32, 63, 64, 255, 256, M - 257, M - 256, M - 65, M - 33, M - 2, M - 1]
-    rows = sorted(set([r for r in edge if 0 <= r < M] + list(rng.integers(0, M, size=n))))
-    return np.array(rows, dtype=np.int64)
+    bands = [min(M - 1, b + int(rng.integers(0, 32))) for b in range(0, M, 32)]
+    return np.array(sorted(set([r for r in edge if 0 <= r < M] + bands)), dtype=np.int64)
 
 
 @pytest.mark.parametrize("name,tile_list", CASES)
-def test_full_size_sampled_rows(name, tile_list):
+def test_full_size_whole_c(name, tile_list):
+    """Every element of C, for each listed instance, against the oracle's fp64 result; and every other
+    compiled instance bit for bit against the first listed one (all instances add the products of one
+    element in the same order, so their roundings agree), which extends the element-wise check to all of them."""
     import torch
     cfg = workloads.CONFIGS[name]
     print(f"full-size {name}: generating", flush=True)
@@ -40,25 +50,38 @@ def test_full_size_sampled_rows(name, tile_list):
     mant, expo = oracle.quantize(A)
     assert np.array_equal(gm, mant) and np.array_equal(ge, expo) and not pad.any()    # quantiser bit-exact at full size
     del A, gm, ge
-    rows = _sample_rows(M, np.random.default_rng(1))
-    print(f"full-size {name}: oracle gemm on {rows.size} rows", flush=True)
-    C_ref, T, _ = oracle.gemm(mant, expo, Bb, rows=rows)
-    ref = oracle.bf16_to_double(C_ref)
-    tol = oracle.tolerance(T)
     B_dev = bits_to_bf16_tensor(Bb, "cuda")
-    rows_t = torch.from_numpy(rows).cuda()
+    results = []
     for tiles in tile_list:
-        print(f"full-size {name}: tiles {tiles}", flush=True)
         C = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
         g = atb.Gemm(M, N, K, *tiles)
         g.run(A_bfp, B_dev, C)
         torch.cuda.synchronize()
-        assert not torch.isnan(C).any().item(), f"{name} {tiles}: unwritten outputs"
-        got = oracle.bf16_to_double(bf16_tensor_bits(C[rows_t]))
-        err = np.abs(got - ref)
-        assert not (err > tol).any(), f"{name} {tiles}: worst ratio {np.max(err / tol):.3g}"
         g.close()
+        assert not torch.isnan(C).any().item(), f"{name} {tiles}: unwritten outputs"
+        results.append(C)
+    first = results[0].view(torch.int16)
+    for tiles in atb.instances():
+        if tiles in tile_list:
+            continue
+        C = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        g = atb.Gemm(M, N, K, *tiles)
+        g.run(A_bfp, B_dev, C)
+        torch.cuda.synchronize()
+        g.close()
+        assert torch.equal(C.view(torch.int16), first), f"{name}: instance {tiles} differs from {tile_list[0]}"
         del C
+    t0 = time.perf_counter()
+    for r0 in range(0, M, ORACLE_CHUNK):
+        r1 = min(M, r0 + ORACLE_CHUNK)
+        C_ref, T, _ = oracle.gemm(mant[r0:r1], expo[r0:r1], Bb)
+        ref = oracle.bf16_to_double(C_ref)
+        tol = oracle.tolerance(T)
+        print(f"full-size {name}: oracle rows {r0}..{r1 - 1} after {time.perf_counter() - t0:.1f} s", flush=True)
+        for tiles, C in zip(tile_list, results):
+            got = oracle.bf16_to_double(bf16_tensor_bits(C[r0:r1]))
+            err = np.abs(got - ref)
+            assert not (err > tol).any(), f"{name} {tiles} rows {r0}..{r1 - 1}: worst ratio {np.max(err / tol):.3g}"
 
 
 @pytest.mark.parametrize("name,tiles", [("square4096", (128, 256, 64, 256)), ("square8192", (128, 256, 64, 256)), ("square8192", (256, 256, 64, 256))])
@@ -81,7 +104,7 @@ def test_full_size_all_bfp16_sampled_rows(name, tiles):
     assert np.array_equal(gm, bmant) and np.array_equal(ge, bexpo)
     del A, Bt, gm, ge
     Bq_bits = np.ascontiguousarray(oracle.bfp16_as_bf16_bits(bmant, bexpo).T)
-    rows = _sample_rows(M, np.random.default_rng(2), n=24)
+    rows = _band_rows(M, np.random.default_rng(2))
     print(f"full-size all-BFP16 {name}: oracle gemm on {rows.size} rows", flush=True)
     _, T, S, _ = oracle.gemm(mant, expo, Bq_bits, rows=rows, want_sum=True)
     C = torch.full((atb.bfp16_bytes(M, N),), 0xAB, dtype=torch.uint8, device="cuda")
