@@ -161,6 +161,50 @@ def time_per_launch(plan, sets, launches):
     return [evs[i].elapsed_time(evs[i + 1]) for i in range(launches)]
 
 
+def read_sclk_mhz():
+    """Current shader clock as the driver reports it (the starred level of pp_dpm_sclk), or None."""
+    import glob
+    for f in glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk"):
+        try:
+            for line in open(f):
+                if "*" in line:
+                    return int(line.split(":")[1].strip().lower().split("mhz")[0])
+        except Exception:
+            pass
+    return None
+
+
+def clock_under(launch, launches):
+    """Median of the driver-reported shader clock while `launch()` is called `launches` times back to back
+    (sampled from a second thread every few ms; not part of any timed region).  None if it cannot be read."""
+    import threading
+    import torch
+    if read_sclk_mhz() is None:
+        return None
+    samples, stop = [], []
+
+    def sampler():
+        while not stop:
+            v = read_sclk_mhz()
+            if v:
+                samples.append(v)
+            time.sleep(0.004)
+
+    for _ in range(launches // 4):
+        launch()
+    torch.cuda.synchronize()
+    th = threading.Thread(target=sampler)
+    th.start()
+    for _ in range(launches):
+        launch()
+    torch.cuda.synchronize()
+    stop.append(1)
+    th.join()
+    samples.sort()
+    return {"median_mhz": samples[len(samples) // 2], "min_mhz": samples[0], "max_mhz": samples[-1],
+            "samples": len(samples)} if samples else None
+
+
 def time_tiles(atb, M, N, K, tiles, A_bfp, B, C, steps, warmup):
     """Mean kernel ms of one instance on resident operands."""
     p = atb.Gemm(M, N, K, *tiles)
@@ -266,6 +310,7 @@ def main():
               "cold_cache": {"operand_sets": n_sets, "bytes_per_set": int(set_bytes), "launches": len(cold),
                              "median_ms": round(cold[len(cold) // 2], 4),
                              "tflops": round(flop / (cold[len(cold) // 2] * 1e-3) / 1e12, 1)}}
+    clock = None if args.no_sweep else clock_under(lambda: plan.run(A_bfp, B, C), 300)
     plan.close()
 
     traffic, traffic_src = hbm_traffic(args.workload, tiles)
@@ -304,7 +349,9 @@ def main():
         # What the matrix pipes sustain with nothing else going on: an MFMA-only loop on register operands, one
         # workgroup of 8 waves per CU, pseudo-random bf16 operands (and constant ones: less power, higher clock).
         # clock_mhz_from_mfma_rate: the loop's MFMAs follow each other back to back, 32 cycles each per SIMD, so the
-        # shader clock under that load is at least (MFMAs per SIMD * 32) / time; the kernel's two clock counters beside it.
+        # shader clock under that load is at least (MFMAs per SIMD * 32) / time; the kernel's two clock counters beside it
+        # (s_memtime ticks once per two shader cycles on this chip: with constant operands 2 * ticks / time reads 2.42 GHz,
+        # the top clock; s_memrealtime is a constant-rate counter).
         sink = torch.empty(256 * 512, dtype=torch.float32, device="cuda")
         clk = torch.zeros(2, dtype=torch.int64, device="cuda")
         probe = {}
@@ -323,7 +370,15 @@ def main():
             ticks = clk.cpu().numpy()
             probe[name] = {"tflops": round(pflop / (ms * 1e-3) / 1e12, 1), "kernel_ms": round(ms, 4),
                            "clock_mhz_from_mfma_rate": round(2 * iters * 32 * 32 / (ms * 1e-3) / 1e6, 0),
-                           "s_memtime_ticks": int(ticks[0]), "s_memrealtime_ticks_100mhz": int(ticks[1])}
+                           "s_memtime_ticks": int(ticks[0]), "s_memrealtime_ticks": int(ticks[1])}
+        pclock = clock_under(lambda: atb.mfma_probe(sink, clk, 256, 800, True), 300)
+        # achieved shader clock (driver-reported, pp_dpm_sclk) under the GEMM and under the MFMA-only loop, and the share
+        # of that clock's matrix throughput the GEMM reaches (256 CUs x 4 SIMDs x 1024 flop per cycle)
+        if clock and pclock:
+            out["shader_clock"] = {"source": "pp_dpm_sclk, sampled while the kernel runs back to back (outside the timed region)",
+                                   "under_gemm": clock, "under_mfma_probe_random_bf16": pclock,
+                                   "probe_clock_mhz_from_s_memtime": round(2 * probe["random_bf16"]["s_memtime_ticks"] / (probe["random_bf16"]["kernel_ms"] * 1e3), 0),
+                                   "gemm_mfma_busy_implied": round(kernel_tflops * 1e12 / (clock["median_mhz"] * 1e6 * 256 * 4 * 1024), 4)}
         out["mfma_probe"] = probe
         meas_peak = probe["random_bf16"]["tflops"]
         out["pct_of_measured_mfma_peak"] = round(100.0 * kernel_tflops / meas_peak, 2)
@@ -464,11 +519,16 @@ def main():
             meas = {t: fl / (time_tiles(atb, Mx, Nx, Kx, t, Ab, Bd, Cd, 30, 15) * 1e-3) / 1e12 for t in inst}
             best = max(meas, key=meas.get)
             pick = rk[0].tiles()
+            # the paper's formulas alone (atb_model_eval: Eqs. 1, 2, 11, 12, 15 with the MI355X constants, none of the
+            # measured per-instance factors the selector adds)
+            pure = {t: atb.model_eval(Mx, Nx, Kx, *t).pred_flops for t in inst}
             held.append({"M": Mx, "N": Nx, "K": Kx, "pick": list(pick), "pick_tflops": round(meas[pick], 1),
                          "pick_model_tflops": round(prd[pick], 1), "best": list(best), "best_tflops": round(meas[best], 1),
                          "pick_vs_best": round(meas[pick] / meas[best], 4),
                          "spearman": round(spearman([prd[t] for t in inst], [meas[t] for t in inst]), 3),
-                         "kendall_tau": round(kendall([prd[t] for t in inst], [meas[t] for t in inst]), 3)})
+                         "kendall_tau": round(kendall([prd[t] for t in inst], [meas[t] for t in inst]), 3),
+                         "spearman_formulas_only": round(spearman([pure[t] for t in inst], [meas[t] for t in inst]), 3),
+                         "kendall_tau_formulas_only": round(kendall([pure[t] for t in inst], [meas[t] for t in inst]), 3)})
             del Ab, Bd, Cd
         out["held_out_shapes"] = {"scope": "out-of-sample: no constant of the selector was fitted on these shapes",
                                   "instances_timed": len(atb.instances()), "shapes": held}

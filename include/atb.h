@@ -282,7 +282,8 @@ atb_status atb_instance_geometry(int index, int *wave_m, int *wave_n, int *wg_pe
  * sink_dev: DEVICE, at least workgroups * 512 * 4 bytes, overwritten (keeps the
  * arithmetic alive).  clocks_dev: DEVICE or NULL; two uint64 written by the
  * first wave: the kernel's length in ticks of the shader-clock counter
- * (s_memtime) and of the constant 100 MHz counter (s_memrealtime).
+ * (s_memtime; measured on MI355X: one tick per two shader cycles) and of the
+ * constant-rate counter (s_memrealtime).
  * *flop (HOST, may be NULL) receives the floating-point operations of the
  * launch.  Async on hip_stream; workgroups in [1, 65536], iters in [1, 2^20]. */
 atb_status atb_mfma_probe(void *sink_dev, void *clocks_dev, int workgroups, int iters,

@@ -55,7 +55,7 @@ __global__ void __launch_bounds__(kProbeThreads) mfma_probe_kernel(float *sink, 
     sink[(size_t)blockIdx.x * kProbeThreads + threadIdx.x] = s;
     if (clocks && blockIdx.x == 0 && threadIdx.x == 0) {
         clocks[0] = c1 - c0;      // s_memtime ticks
-        clocks[1] = w1 - w0;      // s_memrealtime ticks (constant 100 MHz)
+        clocks[1] = w1 - w0;      // s_memrealtime ticks (constant rate)
     }
 }
 
