@@ -116,8 +116,9 @@ typedef enum atb_format {
  *                   the tail of the last panel (columns N .. 64 * panels - 1) is
  *                   written as zero, so the buffer is a valid operand as it is.
  * c_format BFP16 needs N % 8 == 0 (whole blocks; else ATB_ERR_INVALID_ARG);
- * formats other than (BF16, BF16) need an instance that carries the variants: all but (32, 256, 64, 256),
- * (32, 256, 128, 256), (32, 64, 256, 64) and (32, 32, 256, 64) (else ATB_ERR_BAD_TILE).  All else as atb_gemm_create. */
+ * formats other than (BF16, BF16) need an instance that carries the variants: all but (32, 256, 64, 256) and
+ * (32, 256, 128, 256), whose four waves of 256 accumulator registers leave none for a second staging pipeline
+ * (else ATB_ERR_BAD_TILE).  All else as atb_gemm_create. */
 atb_status atb_gemm_create_fmt(atb_gemm **out, int64_t M, int64_t N, int64_t K,
                                int T_MA, int T_MC, int T_K, int T_N,
                                atb_format b_format, atb_format c_format);

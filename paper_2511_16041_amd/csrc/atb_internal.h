@@ -33,7 +33,7 @@ struct Instance {
     int threads;            // wave_m * wave_n * 64
     int lds_bytes;          // static LDS of the kernel
     int wg_per_cu;          // workgroups of this instance that share a CU
-    double eff_scale;       // measured microkernel efficiency of this instance relative to Eq. (12)'s fit
+    double eff_scale;       // measured full-load throughput of this instance relative to Eq. (12)'s fit; 0: taken from the issue model
     double lone_cap;        // measured largest gain of a workgroup in a sparsely filled round; 0: the default for wg_per_cu
     hipError_t (*launch)(const GemmParams &p, hipStream_t stream);
     // other storage formats (b_format, c_format as in atb_format); null where the instance has none

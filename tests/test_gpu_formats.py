@@ -18,7 +18,7 @@ pytestmark = pytest.mark.gpu
 
 FMT_TILES = [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256),
              (128, 128, 64, 256), (64, 128, 64, 256), (128, 128, 64, 128), (64, 128, 64, 128), (64, 64, 64, 64), (32, 64, 64, 64),
-             (64, 64, 128, 128)]
+             (64, 64, 128, 128), (32, 64, 256, 64), (32, 32, 256, 64)]
 COMBOS = [("bfp16", "bf16"), ("bf16", "bfp16"), ("bfp16", "bfp16")]
 
 
@@ -125,6 +125,33 @@ def test_bfp16_b_with_ragged_n(tiles, shape):
     got = _run(mant, expo, (bmant, bexpo), M, N, K, tiles, "bfp16", "bf16")
     err = np.abs(oracle.bf16_to_double(got) - oracle.bf16_to_double(C_ref))
     assert not np.isnan(err).any() and not (err > oracle.tolerance(T)).any()
+
+
+@pytest.mark.parametrize("tiles", [(32, 64, 256, 64), (32, 32, 256, 64)])
+@pytest.mark.parametrize("fmt", COMBOS)
+@pytest.mark.parametrize("shape", [(16, 520, 776), (64, 264, 1032), (9, 72, 256)])
+def test_skinny_problems_with_bfp16_weights(tiles, fmt, shape):
+    """Few rows of activations against a wide weight matrix stored as BFP16 (the paper's Config 1 orientation is this
+    problem transposed): the instances built for skinny problems, on tiles that lie mostly beyond M."""
+    b_format, c_format = fmt
+    M, N, K = shape
+    print(f"formats skinny {shape} tiles={tiles} B={b_format} C={c_format}", flush=True)
+    A, Bt = _inputs(M, N, K, seed=9, exact=False)
+    mant, expo, bmant, bexpo, Bq_bits = _reference(A, Bt)
+    C_ref, T, S, _ = oracle.gemm(mant, expo, Bq_bits, want_sum=True)
+    B_arg = (bmant, bexpo) if b_format == "bfp16" else Bq_bits
+    got = _run(mant, expo, B_arg, M, N, K, tiles, b_format, c_format)
+    tol = oracle.tolerance(T)
+    if c_format == "bfp16":
+        cm, ce, pad = got
+        step = np.repeat(np.ldexp(1.0, ce.astype(np.int64) - 134), 8, axis=1)
+        err = np.abs(oracle.decode(cm, ce) - S)
+        assert not (err > tol + step).any(), f"worst {np.max(err / (tol + step)):.3g}"
+        assert not pad.any()
+    else:
+        err = np.abs(oracle.bf16_to_double(got) - oracle.bf16_to_double(C_ref))
+        assert not np.isnan(err).any()
+        assert not (err > tol).any(), f"worst ratio {np.max(err / tol):.3g}"
 
 
 def test_format_argument_errors():
