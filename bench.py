@@ -389,10 +389,13 @@ def main():
     sweep = []
     if not args.no_sweep:
         pred = {c.tiles(): c.pred_flops / 1e12 for c in ranked}
+        p0 = atb.Gemm(M, N, K, *tiles)
+        burn_in(p0, A_bfp, B, C, 0.1)           # the probe above left the chip in another power state
+        p0.close()
         for t in atb.instances():
             if t[1] != tiles[1] and (M * N) // (t[1] * t[3]) > 65536:
                 continue
-            kms = time_tiles(atb, M, N, K, t, A_bfp, B, C, max(5, args.steps // 2), 5)
+            kms = time_tiles(atb, M, N, K, t, A_bfp, B, C, max(5, args.steps // 2), 10)
             sweep.append(entry(t, flop, kms, pred.get(t, 0.0)))
         sym = [s for s in sweep if s["rho"] == 1 and s["tiles"][1:] == list(tiles[1:])]
         best_atb = max([s for s in sweep if s["rho"] > 1 and s["tiles"][1:] == list(tiles[1:])],
