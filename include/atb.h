@@ -245,7 +245,7 @@ atb_status atb_select_tiles(int64_t M, int64_t N, int64_t K, const atb_hw_params
  * measured clock follows 1.339 GHz * mfma_util^-0.617 (capped at 2.4), and
  * pred_flops = flop per K-step * CUs / (kstep / clock).
  * Predicts the full-load throughput of the compiled instances within 15 %
- * from the tile factors and the wave grid alone (tests/golden/mi355x_instances.txt);
+ * from the tile factors and the wave grid alone (measured values: tests/measured/mi355x_instances.txt);
  * it does not see pipeline stalls of a particular schedule. */
 typedef struct atb_micro_model {
     double n_mfma;         /* MFMAs per C tile and K-step */

@@ -194,7 +194,7 @@ def test_microkernel_model_against_measurements():
     measured full-load throughput and MFMA-busy fraction of every compiled instance."""
     import os
     rows = []
-    for line in open(os.path.join(os.path.dirname(__file__), "golden", "mi355x_instances.txt")):
+    for line in open(os.path.join(os.path.dirname(__file__), "measured", "mi355x_instances.txt")):
         if line.startswith("#") or not line.strip():
             continue
         f = line.split()
@@ -264,7 +264,7 @@ def test_selector_against_measured_sweep():
     predicted throughput of the pick within 30 % of its measurement (20 % but for M = 16)."""
     import os
     inst = atb.instances()
-    rows = [l.split() for l in open(os.path.join(os.path.dirname(__file__), "golden", "mi355x_shape_sweep.txt"))
+    rows = [l.split() for l in open(os.path.join(os.path.dirname(__file__), "measured", "mi355x_shape_sweep.txt"))
             if l.strip() and not l.startswith("#")]
     assert len(rows) == 20
     for f in rows:
