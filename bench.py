@@ -396,7 +396,13 @@ def main():
             if t[1] != tiles[1] and (M * N) // (t[1] * t[3]) > 65536:
                 continue
             kms = time_tiles(atb, M, N, K, t, A_bfp, B, C, max(5, args.steps // 2), 10)
-            sweep.append(entry(t, flop, kms, pred.get(t, 0.0)))
+            e = entry(t, flop, kms, pred.get(t, 0.0))
+            # the microkernel issue model's full-load figure for this instance (tile factors and wave grid only)
+            geom = atb.instance_geometry(atb.instances().index(t))
+            mm = atb.model_microkernel(*t, *geom)
+            e["issue_model_tflops"] = round(mm.pred_flops / 1e12, 1)
+            e["issue_model_mfma_busy"] = round(mm.mfma_util, 3)
+            sweep.append(e)
         sym = [s for s in sweep if s["rho"] == 1 and s["tiles"][1:] == list(tiles[1:])]
         best_atb = max([s for s in sweep if s["rho"] > 1 and s["tiles"][1:] == list(tiles[1:])],
                        key=lambda s: s["tflops"], default=None)

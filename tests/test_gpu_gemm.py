@@ -210,7 +210,7 @@ def test_graph_capture_and_replay():
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
-        layers()                                # first launches outside the capture (occupancy queries, lazy loading)
+        layers()                                # first launches outside the capture (the runtime loads a kernel's code lazily)
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     want = bf16_tensor_bits(y)
