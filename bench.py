@@ -43,6 +43,8 @@ def parse_args():
     ap.add_argument("--workload", default="square8192")
     ap.add_argument("--tiles", default="", help="T_MA,T_MC,T_K,T_N (default: the selector's pick)")
     ap.add_argument("--shape", default="", help="M,N,K: the workload's input recipe at another size (for profiles of other shapes)")
+    ap.add_argument("--b-format", default="bf16", choices=["bf16", "bf16_t"],
+                    help="layout of B for the timed plan: bf16 = K x N row-major (the default), bf16_t = handed over transposed (N x K)")
     ap.add_argument("--no-sweep", action="store_true", help="headline only: skip the sweeps, the other workloads and the probe")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle (baseline and output checks)")
     ap.add_argument("--cpu-rows", type=int, default=4096, help="rows of C the oracle computes for the CPU baseline")
@@ -290,7 +292,10 @@ def main():
     parity_worst = 0.0
 
     raw_a = A_bfp.cpu().numpy() if not args.no_cpu else None
-    plan = atb.Gemm(M, N, K, *tiles)
+    B_rowmajor = B
+    if args.b_format == "bf16_t":
+        B = B_rowmajor.t().contiguous()                # the timed plan takes B^T; everything after it takes B again
+    plan = atb.Gemm(M, N, K, *tiles, b_format=args.b_format)
     info = plan.launch_info()
     burn_in(plan, A_bfp, B, C)
     wall, kernel_ms = time_plan(plan, A_bfp, B, C, args.steps, args.warmup)
@@ -312,6 +317,7 @@ def main():
                              "tflops": round(flop / (cold[len(cold) // 2] * 1e-3) / 1e12, 1)}}
     clock = None if args.no_sweep else clock_under(lambda: plan.run(A_bfp, B, C), 300)
     plan.close()
+    B = B_rowmajor
 
     traffic, traffic_src = hbm_traffic(args.workload, tiles)
     out = {
@@ -331,6 +337,7 @@ def main():
                    "tiles": {"T_MA": tiles[0], "T_MC": tiles[1], "T_K": tiles[2], "T_N": tiles[3]},
                    "rho": tiles[1] // tiles[0], "workgroups": info.workgroups, "threads": info.threads,
                    "lds_bytes": info.lds_bytes, "a_format": "BFP16 (int8 mantissa + shared uint8 exponent per 8)",
+                   "b_format": "bf16, K x N row-major" if args.b_format == "bf16" else "bf16, handed over transposed (N x K)",
                    "accumulate": "fp32", "out": "bf16"},
         "pct_of_bf16_peak": round(100.0 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": {"bound": "mfma", "achieved": round(kernel_tflops, 2), "peak": PEAK_BF16_TFLOPS,
@@ -426,13 +433,15 @@ def main():
         # the other storage formats of the same tile (B handed over as B^T in BFP16, C written as BFP16)
         Bt_bfp = atb.bfp16_quantize(B.float().t().contiguous())
         fmts = []
-        for bf, cf in (("bfp16", "bf16"), ("bf16", "bfp16"), ("bfp16", "bfp16")):
+        Bt = B.t().contiguous()
+        for bf, cf in (("bf16_t", "bf16"), ("bfp16", "bf16"), ("bf16", "bfp16"), ("bfp16", "bfp16")):
             p = atb.Gemm(M, N, K, *tiles, b_format=bf, c_format=cf)
             Cx = None if cf == "bf16" else torch.empty(atb.bfp16_bytes(M, N), dtype=torch.uint8, device="cuda")
-            _, kms = time_plan(p, A_bfp, Bt_bfp if bf == "bfp16" else B, Cx if Cx is not None else C, max(5, args.steps // 2), 5)
+            Bx = Bt_bfp if bf == "bfp16" else Bt if bf == "bf16_t" else B
+            _, kms = time_plan(p, A_bfp, Bx, Cx if Cx is not None else C, max(5, args.steps // 2), 5)
             p.close()
             fmts.append({"A": "bfp16", "B": bf, "C": cf, "accumulate": "fp32", "tflops": round(flop / (kms * 1e-3) / 1e12, 1)})
-        del Bt_bfp
+        del Bt_bfp, Bt
         out["storage_formats"] = fmts
 
     # CPU baseline: the oracle on the first rows of the headline problem, and the timed output against those rows

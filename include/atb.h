@@ -98,7 +98,8 @@ void atb_gemm_destroy(atb_gemm *g);
  * A is always BFP16; accumulation is always fp32 in the MFMA accumulators. */
 typedef enum atb_format {
     ATB_FMT_BF16 = 0,
-    ATB_FMT_BFP16 = 1
+    ATB_FMT_BFP16 = 1,
+    ATB_FMT_BF16_T = 2      /* B only: bf16, handed over transposed (see atb_gemm_create_fmt) */
 } atb_format;
 
 /* atb_gemm_create with a storage format per operand.  The plan is run with
@@ -109,6 +110,14 @@ typedef enum atb_format {
  *                   reduction dimension, as the format requires, Sec. 2.4)
  *                   with the K index contiguous; atb_bfp16_quantize of a
  *                   row-major N x K fp32 matrix produces it.
+ *   b_format BF16_T: B^T, N x K bf16 row-major (leading dimension K, the K index
+ *                   contiguous) -- the layout in which frameworks keep the weight of a
+ *                   linear layer.  The kernel then reads its B fragments with plain
+ *                   16-byte LDS reads instead of transposing ones (half the LDS read
+ *                   instructions for B).  Same values, same summation order, same
+ *                   result bits as b_format BF16.  Needs c_format BF16, an instance
+ *                   with T_K = 64 and a C tile of at least 128 x 256, and
+ *                   2 * T_N * K < 2^31 (else ATB_ERR_BAD_TILE / ATB_ERR_INVALID_ARG).
  *   c_format BF16 : C, M x N bf16 row-major.
  *   c_format BFP16: C as a BFP16 buffer with the layout atb_bfp16_layout(M, N)
  *                   (blocks of 8 along N), quantised from the fp32

@@ -267,13 +267,14 @@ class LaunchInfo:
     lds_bytes: int
 
 
-FORMATS = {"bf16": 0, "bfp16": 1}      # atb_format
+FORMATS = {"bf16": 0, "bfp16": 1, "bf16_t": 2}      # atb_format
 
 
 class Gemm:
     """A plan from atb_gemm_create / atb_gemm_create_fmt; run() launches it asynchronously.
 
     b_format "bfp16": run() takes B^T (N x K) as a BFP16 buffer (bfp16_quantize of the N x K matrix);
+    b_format "bf16_t": run() takes B^T as a bf16 tensor of shape (N, K);
     c_format "bfp16": run() returns C as a BFP16 buffer with the layout bfp16_layout(M, N)."""
 
     def __init__(self, M: int, N: int, K: int, T_MA: int, T_MC: int, T_K: int, T_N: int,
@@ -294,6 +295,8 @@ class Gemm:
         assert A_bfp.is_cuda and A_bfp.dtype == torch.uint8 and A_bfp.numel() == bfp16_bytes(M, K)
         if self.b_format == "bf16":
             assert B.is_cuda and B.dtype == torch.bfloat16 and tuple(B.shape) == (K, N) and B.is_contiguous()
+        elif self.b_format == "bf16_t":
+            assert B.is_cuda and B.dtype == torch.bfloat16 and tuple(B.shape) == (N, K) and B.is_contiguous()
         else:
             assert B.is_cuda and B.dtype == torch.uint8 and B.numel() == bfp16_bytes(N, K)
         if self.c_format == "bf16":

@@ -114,8 +114,10 @@ extern "C" atb_status atb_gemm_create_fmt(atb_gemm **out, int64_t M, int64_t N, 
     if (!out) return ATB_ERR_INVALID_ARG;
     *out = nullptr;
     if (M < 1 || N < 1 || K < 8 || (K % 8) != 0) return ATB_ERR_INVALID_ARG;
-    if ((b_format != ATB_FMT_BF16 && b_format != ATB_FMT_BFP16) || (c_format != ATB_FMT_BF16 && c_format != ATB_FMT_BFP16))
+    if ((b_format != ATB_FMT_BF16 && b_format != ATB_FMT_BFP16 && b_format != ATB_FMT_BF16_T) ||
+        (c_format != ATB_FMT_BF16 && c_format != ATB_FMT_BFP16))
         return ATB_ERR_INVALID_ARG;
+    if (b_format == ATB_FMT_BF16_T && c_format != ATB_FMT_BF16) return ATB_ERR_INVALID_ARG;
     const bool other_fmt = (b_format != ATB_FMT_BF16 || c_format != ATB_FMT_BF16);
     if (c_format == ATB_FMT_BFP16 && (N % 8) != 0) return ATB_ERR_INVALID_ARG;   // whole blocks along N
     if (N * atb::round_up(K, 64) >= ((int64_t)1 << 31) || M * atb::round_up(N, 64) >= ((int64_t)1 << 31))
@@ -135,6 +137,11 @@ extern "C" atb_status atb_gemm_create_fmt(atb_gemm **out, int64_t M, int64_t N, 
     const int idx = atb::find_instance(T_MA, T_MC, T_K, T_N);
     if (idx < 0) return ATB_ERR_BAD_TILE;
     if (other_fmt && atb::instance(idx).launch_fmt == nullptr) return ATB_ERR_BAD_TILE;
+    if (b_format == ATB_FMT_BF16_T) {
+        if (!atb::instance(idx).has_b_transposed) return ATB_ERR_BAD_TILE;
+        // byte offsets of a B^T tile's requests relative to its first row are 32-bit
+        if ((int64_t)2 * T_N * K >= ((int64_t)1 << 31)) return ATB_ERR_INVALID_ARG;
+    }
 
     atb_gemm *g = new (std::nothrow) atb_gemm;
     if (!g) return ATB_ERR_NOMEM;
@@ -163,7 +170,7 @@ extern "C" atb_status atb_gemm_create_fmt(atb_gemm **out, int64_t M, int64_t N, 
         std::fprintf(stderr, "atb_gemm_create: M=%lld N=%lld K=%lld T_MA=%d T_MC=%d T_K=%d T_N=%d rho=%d b=%s c=%s "
                              "instance=%d waves=%dx%d threads=%d lds=%d tiles=%dx%d group_m=%d k_panels=%d\n",
                      (long long)M, (long long)N, (long long)K, T_MA, T_MC, T_K, T_N, T_MC / T_MA,
-                     b_format == ATB_FMT_BFP16 ? "bfp16" : "bf16", c_format == ATB_FMT_BFP16 ? "bfp16" : "bf16", idx,
+                     b_format == ATB_FMT_BFP16 ? "bfp16" : b_format == ATB_FMT_BF16_T ? "bf16_t" : "bf16", c_format == ATB_FMT_BFP16 ? "bfp16" : "bf16", idx,
                      x.wave_m, x.wave_n, x.threads, x.lds_bytes, p.tiles_m, p.tiles_n, p.group_m, p.k_panels);
     }
     *out = g;

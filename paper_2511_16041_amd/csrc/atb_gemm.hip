@@ -192,7 +192,11 @@ ATB_DEV bool tile_origin(const GemmParams &p, int t, int &tm0, int &tn0)
 // does the same for A -- and its fragments are plain 16-byte LDS reads.  Tile kt is fetched in the
 // first phase of K-step kt-3, decoded during K-step kt-2, read into fragment registers in the last
 // band of K-step kt-1.  CBFP: the epilogue quantises C to BFP16 in blocks of 8 along N.
-template <class S, bool VEC, int ROLE, bool BBFP = false, bool CBFP = false, bool SK = false>
+// BTR: B arrives as bf16 but transposed, B^T (N x K, the K index contiguous: the layout in which frameworks keep the
+// weight of a linear layer).  Its tile still goes global -> LDS directly, now as [n][k] rows of 2 T_K bytes whose
+// 16-byte chunks are XOR-swizzled by (n / 2) mod 8, and an MFMA fragment is ONE plain 16-byte LDS read per lane
+// instead of two transposing 8-byte reads (half the LDS read instructions for B).
+template <class S, bool VEC, int ROLE, bool BBFP = false, bool CBFP = false, bool SK = false, bool BTR = false>
 struct TileKernel {
     static constexpr int NTS = S::NTS, ACE = S::ACE, A_CPR = S::A_CPR;
     static constexpr int AO = BBFP ? S::A_SLABS : S::AO;                                 // with B in BFP16 the second group has its hands full
@@ -224,6 +228,8 @@ struct TileKernel {
     static_assert(!BBFP || (NPAIR_B % S::RHO == 0 && S::T_K % 16 == 0 && (S::T_N * S::T_K / 16) % NTS == 0), "BFP16 B staging must split evenly");
     static_assert(!BBFP || S::LDS_BYTES_BT <= 160 * 1024, "LDS budget of a gfx950 CU (the BFP16 B path always has two buffers)");
     static_assert((ROLE == 0) == (S::CW != 8 && S::HW == 0) && (ROLE >= 3) == (S::HW > 0), "two staging groups exactly when two waves share a SIMD; helper roles exactly with helper waves");
+    static_assert(!BTR || (VEC && !BBFP && !SK && S::T_K == 64), "the transposed-B path: bf16 B^T, K-steps of 64 (8 chunks per LDS row, swizzled over 8 row pairs)");
+    static constexpr int PBT = S::T_K * 2;                                                // LDS pitch of a B^T tile row
 
     const GemmParams &p;
     Rsrc rs;
@@ -237,7 +243,8 @@ struct TileKernel {
     int b_t, b_n0, b_steps;            // B requests: likewise with the column origin
     // LDS byte addresses of this thread's staging writes and fragment reads, per buffer
     char *a_wr[S::AB], *b_wr[2];
-    const char *a_rd[S::AB], *b_rd[2][S::NBASE];  // b_rd[buffer][column band mod 4]
+    static constexpr int NRD = BTR ? S::KS : S::NBASE;
+    const char *a_rd[S::AB], *b_rd[2][NRD];       // b_rd[buffer][column band mod 4]; transposed B: b_rd[buffer][k-slice]
     char *b_req[2];                    // LDS byte address of this wave's first 1 KiB B request, per buffer
     int b_fill_off, b_read_off;        // NB > 2: byte offsets of the ring buffers being filled / read next (wave-uniform)
     // Byte offsets of this thread's global loads relative to the current K-step.  They never
@@ -307,9 +314,18 @@ struct TileKernel {
             // of those 4 rows.  The swizzle of row r (mod 4) permutes the chunk index, so each of the
             // first NBASE column bands gets its own per-lane base; band nt >= 4 adds (nt / 4) * 256 bytes.
 #pragma unroll
-            for (int e = 0; e < S::NBASE; ++e) {
-                const int chunk = 4 * (wn * S::NTW + e) + 2 * (blk & 1) + ((j & 3) >> 1);
-                b_rd[b][e] = b_base + (8 * (blk >> 1) + r) * S::PB + ((chunk ^ (r << S::SWZ)) * 16) + (j & 1) * 8;
+            for (int e = 0; e < NRD; ++e) {
+                if constexpr (BTR) {
+                    // B^T tile [n][k]: lane l reads column (row of B^T) wn*NTW*32 + l%32 and the chunk of k-slice e
+                    // (e = ks: 8 k values from 16 ks + 8 (l/32)); the chunk sits at position chunk ^ ((n / 2) % 8)
+                    // of its row.  Sixteen lanes (rows n .. n+15) then cover all 64 banks once: row pairs differ in
+                    // the position, the two rows of a pair in the half of the banks (pitch 128 bytes).
+                    const int n = wn * S::NTW * 32 + (lane & 31);
+                    b_rd[b][e] = b_base + n * PBT + (((2 * e + (lane >> 5)) ^ ((n >> 1) & 7)) * 16);
+                } else {
+                    const int chunk = 4 * (wn * S::NTW + e) + 2 * (blk & 1) + ((j & 3) >> 1);
+                    b_rd[b][e] = b_base + (8 * (blk >> 1) + r) * S::PB + ((chunk ^ (r << S::SWZ)) * 16) + (j & 1) * 8;
+                }
             }
         }
         if constexpr (BBFP) {
@@ -353,8 +369,17 @@ struct TileKernel {
 #pragma unroll
         for (int i = 0; i < BPT; ++i) {
             const int slot = slot0 + i * NTS + lane;
-            const int row = slot / S::B_CPR, c = (slot % S::B_CPR) ^ ((row & 3) << S::SWZ);
-            b_off[i] = (row * p.N + c * 8) * 2;
+            if constexpr (BTR) {
+                // slot = 8 * (row n of the B^T tile) + chunk position: the chunk stored there is position ^ ((n / 2) % 8).
+                // Offsets are relative to the tile's first row and the K-step's first k, both of which live in the
+                // descriptor's base (open_b, load_b_chunk).  Rows >= N lie beyond the end of B^T and read as zero; k >= K
+                // runs into the next row, whose (finite) values meet the zero tail of A.
+                const int row = slot / (S::T_K / 8), c = (slot % (S::T_K / 8)) ^ ((row >> 1) & 7);
+                b_off[i] = (row * p.K + c * 8) * 2;
+            } else {
+                const int row = slot / S::B_CPR, c = (slot % S::B_CPR) ^ ((row & 3) << S::SWZ);
+                b_off[i] = (row * p.N + c * 8) * 2;
+            }
         }
 #pragma unroll
         for (int a = 0; a < S::MTW; ++a)
@@ -433,6 +458,11 @@ struct TileKernel {
                 bt_moff[i] += d * kPanelK;
                 bt_eoff[i] += d * (kPanelK / 8);
             }
+        } else if constexpr (BTR) {
+            // the tile's first row goes into the base, not into the offsets: rows are K elements apart, and 32-bit
+            // offsets from the start of B^T would not reach the far end of a large operand
+            b_ptr = p.B + (int64_t)(live ? tn0 : 0) * p.K;
+            b_left = live ? ((int64_t)p.N - tn0) * p.K * 2 : 0;
         } else {
             b_ptr = p.B;
             b_left = live ? (int64_t)p.K * p.N * 2 : 0;
@@ -591,6 +621,9 @@ struct TileKernel {
         if constexpr (i == BPT - 1) {
             if (--b_steps == 0) {
                 open_b(b_t + t_stride);
+            } else if constexpr (BTR) {
+                b_ptr += S::T_K;
+                b_left = max(b_left - (int64_t)S::T_K * 2, (int64_t)0);
             } else {
                 b_ptr += S::T_K * p.N;
                 b_left = max(b_left - (int64_t)S::T_K * p.N * 2, (int64_t)0);
@@ -730,6 +763,9 @@ struct TileKernel {
     {
         if constexpr (BBFP) {
             bfrag[ks][nt] = *reinterpret_cast<const bf16x8 *>(bt_rd[buf] + nt * 32 * S::PA + ks * 32);
+        } else if constexpr (BTR) {
+            const char *base = (S::NB > 2) ? b_rd[0][ks] + b_read_off : b_rd[buf][ks];
+            bfrag[ks][nt] = *reinterpret_cast<const bf16x8 *>(base + nt * 32 * PBT);
         } else {
             const char *base = (S::NB > 2) ? b_rd[0][nt % S::NBASE] + b_read_off : b_rd[buf][nt % S::NBASE];
             const char *src = base + ks * 16 * S::PB + (nt / S::NBASE) * (S::NBASE * 64);
@@ -1045,7 +1081,7 @@ struct TileKernel {
 // persistent: it holds only as many workgroups as fit on the chip at once, and workgroup b serves
 // tiles b / 8, b / 8 + gridDim.x / 8, ... of its XCD's run as one pipeline, so no tile waits for a
 // workgroup launch or for its first operands.
-template <class S, bool VEC, int ROLE, bool BBFP, bool CBFP>
+template <class S, bool VEC, int ROLE, bool BBFP, bool CBFP, bool BTR>
 __device__ __forceinline__ void tile_loop(const GemmParams &p, char *lds)
 {
     const int total = p.tiles_m * p.tiles_n;
@@ -1055,7 +1091,7 @@ __device__ __forceinline__ void tile_loop(const GemmParams &p, char *lds)
     // workgroups of the skinny-problem instances whose tile lies at least half beyond M take the variant
     // that skips dead rows (measured on the other small instances it does not pay: there a wave's chunks
     // are either all live or the block-wise decode costs more than the skipped rows save)
-    if constexpr (S::T_K >= 256 && S::T_MC * S::T_N < 256 * 256 && !BBFP) {
+    if constexpr (S::T_K >= 256 && S::T_MC * S::T_N < 256 * 256 && !BBFP && !BTR) {
         int m0 = 0, n0 = 0;
         tile_origin<S>(p, first, m0, n0);
         if (p.M - m0 <= S::T_MC / 2) {
@@ -1064,27 +1100,27 @@ __device__ __forceinline__ void tile_loop(const GemmParams &p, char *lds)
             return;
         }
     }
-    TileKernel<S, VEC, ROLE, BBFP, CBFP> tile(p, lds, first, (int)gridDim.x / 8);
+    TileKernel<S, VEC, ROLE, BBFP, CBFP, false, BTR> tile(p, lds, first, (int)gridDim.x / 8);
     tile.run();
 }
 
-template <class S, bool VEC, bool BBFP = false, bool CBFP = false>
+template <class S, bool VEC, bool BBFP = false, bool CBFP = false, bool BTR = false>
 __global__ void __launch_bounds__(S::NT) atb_gemm_kernel(const GemmParams p)
 {
     __shared__ __attribute__((aligned(16))) char lds[BBFP ? S::LDS_BYTES_BT : S::LDS_BYTES];
     if constexpr (S::HW > 0) {
         if (threadIdx.x < S::CW * 64)
-            tile_loop<S, VEC, 4, BBFP, CBFP>(p, lds);
+            tile_loop<S, VEC, 4, BBFP, CBFP, BTR>(p, lds);
         else
-            tile_loop<S, VEC, 3, BBFP, CBFP>(p, lds);
+            tile_loop<S, VEC, 3, BBFP, CBFP, BTR>(p, lds);
     } else if constexpr (S::CW == 8) {
         // wave-uniform branch; both sides execute the same sequence of barriers
         if (threadIdx.x < 256)
-            tile_loop<S, VEC, 1, BBFP, CBFP>(p, lds);
+            tile_loop<S, VEC, 1, BBFP, CBFP, BTR>(p, lds);
         else
-            tile_loop<S, VEC, 2, BBFP, CBFP>(p, lds);
+            tile_loop<S, VEC, 2, BBFP, CBFP, BTR>(p, lds);
     } else {
-        tile_loop<S, VEC, 0, BBFP, CBFP>(p, lds);
+        tile_loop<S, VEC, 0, BBFP, CBFP, BTR>(p, lds);
     }
 }
 
@@ -1107,7 +1143,7 @@ inline int compute_units()
     return cached[dev];
 }
 
-template <class S, bool VEC, bool BBFP, bool CBFP>
+template <class S, bool VEC, bool BBFP, bool CBFP, bool BTR = false>
 hipError_t launch_kernel(const GemmParams &p, hipStream_t stream)
 {
     const int total = p.tiles_m * p.tiles_n;
@@ -1125,7 +1161,7 @@ hipError_t launch_kernel(const GemmParams &p, hipStream_t stream)
         if (cus == 0) return hipErrorNoDevice;
         slots = std::min(per_xcd, cus / 8);
     }
-    hipLaunchKernelGGL((atb_gemm_kernel<S, VEC, BBFP, CBFP>), dim3(slots * 8), dim3(S::NT), 0, stream, p);
+    hipLaunchKernelGGL((atb_gemm_kernel<S, VEC, BBFP, CBFP, BTR>), dim3(slots * 8), dim3(S::NT), 0, stream, p);
     return hipGetLastError();
 }
 
@@ -1144,6 +1180,13 @@ template <class S>
 hipError_t launch_instance_fmt(const GemmParams &p, int b_format, int c_format, hipStream_t stream)
 {
     const bool bb = (b_format == ATB_FMT_BFP16), cb = (c_format == ATB_FMT_BFP16);
+    if (b_format == ATB_FMT_BF16_T) {
+        // bf16 B handed over transposed: compiled for the tiles with K-steps of 64 and a bf16 C
+        if constexpr (S::T_K == 64 && S::T_MC * S::T_N >= 128 * 256) {
+            if (!cb) return launch_kernel<S, true, false, false, true>(p, stream);
+        }
+        return hipErrorInvalidValue;
+    }
     if (bb && cb) return launch_kernel<S, true, true, true>(p, stream);
     if (bb) return launch_kernel<S, true, true, false>(p, stream);
     if (cb) return launch_kernel<S, true, false, true>(p, stream);
@@ -1167,6 +1210,7 @@ Instance make_instance(double eff_scale = 0.0, double lone_cap = 0.0)
     i.wg_per_cu = std::max(1, std::min(8, (160 * 1024) / S::LDS_BYTES));   // LDS-limited in every instance
     i.launch = &launch_instance<S>;
     if constexpr (FMT) i.launch_fmt = &launch_instance_fmt<S>; else i.launch_fmt = nullptr;
+    i.has_b_transposed = FMT && S::T_K == 64 && S::T_MC * S::T_N >= 128 * 256;
     return i;
 }
 

@@ -36,6 +36,7 @@ struct Instance {
     double eff_scale;       // measured full-load throughput of this instance relative to Eq. (12)'s fit; 0: taken from the issue model
     double lone_cap;        // measured largest gain of a workgroup in a sparsely filled round; 0: the default for wg_per_cu
     hipError_t (*launch)(const GemmParams &p, hipStream_t stream);
+    bool has_b_transposed;  // launch_fmt also takes b_format = ATB_FMT_BF16_T (with a bf16 C)
     // other storage formats (b_format, c_format as in atb_format); null where the instance has none
     hipError_t (*launch_fmt)(const GemmParams &p, int b_format, int c_format, hipStream_t stream);
 };

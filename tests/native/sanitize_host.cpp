@@ -109,6 +109,7 @@ static void api_paths()
     EXPECT(atb_bfp16_bytes(-5, 8) == 0);
 
     atb_gemm *g = nullptr;
+    alignas(16) static char fake[64];
     EXPECT(atb_gemm_create(nullptr, 64, 64, 64, 32, 64, 64, 64) == ATB_ERR_INVALID_ARG);
     EXPECT(atb_gemm_create(&g, 0, 64, 64, 32, 64, 64, 64) == ATB_ERR_INVALID_ARG && g == nullptr);
     EXPECT(atb_gemm_create(&g, 64, 64, 60, 32, 64, 64, 64) == ATB_ERR_INVALID_ARG);
@@ -122,8 +123,13 @@ static void api_paths()
     EXPECT(atb_gemm_create_fmt(&g, 64, 64, 64, 32, 64, 64, 64, (atb_format)7, ATB_FMT_BF16) == ATB_ERR_INVALID_ARG);
     EXPECT(atb_gemm_create_fmt(&g, 64, 60, 64, 32, 64, 64, 64, ATB_FMT_BF16, ATB_FMT_BFP16) == ATB_ERR_INVALID_ARG);
     EXPECT(atb_gemm_create_fmt(&g, 512, 512, 512, 32, 256, 128, 256, ATB_FMT_BFP16, ATB_FMT_BF16) == ATB_ERR_BAD_TILE);
+    EXPECT(atb_gemm_create_fmt(&g, 512, 512, 512, 32, 64, 64, 64, ATB_FMT_BF16_T, ATB_FMT_BF16) == ATB_ERR_BAD_TILE);
+    EXPECT(atb_gemm_create_fmt(&g, 512, 512, 512, 128, 256, 64, 256, ATB_FMT_BF16_T, ATB_FMT_BFP16) == ATB_ERR_INVALID_ARG);
+    EXPECT(atb_gemm_create_fmt(&g, 512, 512, 512, 128, 256, 64, 256, ATB_FMT_BF16, ATB_FMT_BF16_T) == ATB_ERR_INVALID_ARG);
+    EXPECT(atb_gemm_create_fmt(&g, 512, 500, 512, 128, 256, 64, 256, ATB_FMT_BF16_T, ATB_FMT_BF16) == ATB_OK);
+    EXPECT(atb_gemm_run(g, fake, fake, fake, nullptr) == ATB_ERR_HIP);
+    atb_gemm_destroy(g);
 
-    alignas(16) static char fake[64];
     EXPECT(atb_gemm_create(&g, 3000, 5000, 4104, 256, 256, 64, 256) == ATB_OK && g != nullptr);
     int64_t wg = 0; int th = 0, lds = 0;
     EXPECT(atb_gemm_launch_info(g, &wg, &th, &lds) == ATB_OK && wg == 240 && th == 512 && lds == 139264);

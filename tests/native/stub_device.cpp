@@ -18,6 +18,7 @@ Instance make(int T_MA, int T_MC, int T_K, int T_N, int wm, int wn, int lds, boo
     i.eff_scale = 1.0; i.lone_cap = 0.0;
     i.launch = &no_device;
     i.launch_fmt = fmt ? &no_device_fmt : nullptr;
+    i.has_b_transposed = fmt && T_K == 64 && T_MC * T_N >= 128 * 256;
     return i;
 }
 const Instance g_table[] = {

@@ -166,7 +166,14 @@ def test_create_fmt_validation():
     assert create(512, 508, 256, (128, 256, 64, 256), 0, 1) == 1 and not h.value  # C in BFP16: N % 8 != 0
     assert create(512, 508, 256, (128, 256, 64, 256), 1, 0) == 0 and h.value      # B in BFP16 does not constrain N
     L.atb_gemm_destroy(h)
-    assert create(512, 512, 256, (128, 256, 64, 256), 2, 0) == 1                  # unknown format
+    assert create(512, 512, 256, (128, 256, 64, 256), 3, 0) == 1                  # unknown format
+    assert create(512, 512, 256, (128, 256, 64, 256), 0, 2) == 1                  # "transposed" is a format of B only
+    assert create(512, 508, 256, (128, 256, 64, 256), 2, 0) == 0 and h.value      # bf16 B handed over transposed
+    L.atb_gemm_destroy(h)
+    assert create(512, 512, 256, (128, 256, 64, 256), 2, 1) == 1                  # ... needs a bf16 C
+    assert create(512, 512, 256, (64, 64, 64, 64), 2, 0) == 2                     # ... and one of the large tiles
+    assert create(512, 512, 256, (32, 256, 128, 256), 2, 0) == 2
+    assert create(64, 64, 1 << 23, (128, 256, 64, 256), 2, 0) == 1                # 2 T_N K >= 2^31
     assert create(512, 512, 256, (32, 256, 64, 256), 0, 1) == 2                   # instance without format variants
     assert create(512, 512, 256, (32, 256, 128, 256), 1, 1) == 2
     assert create(64, 512, 1024, (32, 64, 256, 64), 1, 0) == 0 and h.value           # the skinny-problem instances carry the variants

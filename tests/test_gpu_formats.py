@@ -154,6 +154,57 @@ def test_skinny_problems_with_bfp16_weights(tiles, fmt, shape):
         assert not (err > tol).any(), f"worst ratio {np.max(err / tol):.3g}"
 
 
+BT_TILES = [(256, 256, 64, 256), (128, 256, 64, 256), (64, 256, 64, 256), (128, 128, 64, 256), (64, 128, 64, 256)]
+
+
+@pytest.mark.parametrize("tiles", BT_TILES)
+@pytest.mark.parametrize("shape", [(300, 500, 264), (257, 263, 72), (33, 20, 8), (1, 1, 8), (520, 516, 136), (130, 18, 24),
+                                   (700, 1032, 320), (4300, 4400, 136)])
+def test_transposed_bf16_b(tiles, shape):
+    """bf16 B handed over as B^T (N x K): the same values reach the same MFMAs in the same order, so the result must
+    equal the row-major path's bit for bit, besides meeting the oracle's tolerance.  Shapes with ragged M and N, K tails
+    that are not whole K-steps (the tile rows of B^T then run into their neighbours, which meet the zero tail of A), a
+    single block of K, and more tiles than resident workgroups."""
+    import torch
+    M, N, K = shape
+    print(f"formats transposed-B {shape} tiles={tiles}", flush=True)
+    A, Bb = workloads.make_inputs(workloads.CONFIGS["ragged"], M=M, N=N, K=K)
+    mant, expo = oracle.quantize(A)
+    C_ref, T, _ = oracle.gemm(mant, expo, Bb)
+    A_dev = torch.from_numpy(pack_a_bfp(mant, expo, atb.bfp16_layout(M, K))).cuda()
+    B_dev = bits_to_bf16_tensor(Bb, "cuda")
+    Bt_dev = B_dev.t().contiguous()
+    outs = []
+    for fmt, Barg in (("bf16", B_dev), ("bf16_t", Bt_dev)):
+        C = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        g = atb.Gemm(M, N, K, *tiles, b_format=fmt)
+        g.run(A_dev, Barg, C)
+        torch.cuda.synchronize()
+        g.close()
+        outs.append(bf16_tensor_bits(C))
+    err = np.abs(oracle.bf16_to_double(outs[1]) - oracle.bf16_to_double(C_ref))
+    assert not np.isnan(err).any()
+    assert not (err > oracle.tolerance(T)).any(), f"worst ratio {np.max(err / oracle.tolerance(T)):.3g}"
+    assert np.array_equal(outs[0], outs[1]), "transposed-B result differs from the row-major path"
+
+
+@pytest.mark.parametrize("tiles", BT_TILES)
+def test_transposed_bf16_b_exact(tiles):
+    import torch
+    M, N, K = 300, 264, 200
+    A, Bb = workloads.small_integer_inputs(M, N, K, seed=13)
+    mant, expo = oracle.quantize(A)
+    C_ref, _, _ = oracle.gemm(mant, expo, Bb)
+    A_dev = torch.from_numpy(pack_a_bfp(mant, expo, atb.bfp16_layout(M, K))).cuda()
+    Bt_dev = bits_to_bf16_tensor(Bb, "cuda").t().contiguous()
+    C = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    g = atb.Gemm(M, N, K, *tiles, b_format="bf16_t")
+    g.run(A_dev, Bt_dev, C)
+    torch.cuda.synchronize()
+    g.close()
+    assert np.array_equal(bf16_tensor_bits(C), C_ref)
+
+
 def test_format_argument_errors():
     # C in BFP16 needs whole blocks along N
     with pytest.raises(atb.AtbError) as e:

@@ -71,6 +71,19 @@ def test_full_size_whole_c(name, tile_list):
         g.close()
         assert torch.equal(C.view(torch.int16), first), f"{name}: instance {tiles} differs from {tile_list[0]}"
         del C
+    # bf16 B handed over transposed: same bits as the row-major path, at full size too
+    Bt_dev = B_dev.t().contiguous()
+    for tiles in tile_list[:2]:
+        if tiles[2] != 64:
+            continue
+        C = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        g = atb.Gemm(M, N, K, *tiles, b_format="bf16_t")
+        g.run(A_bfp, Bt_dev, C)
+        torch.cuda.synchronize()
+        g.close()
+        assert torch.equal(C.view(torch.int16), results[tile_list.index(tiles)].view(torch.int16)), f"{name} {tiles}: transposed-B path differs"
+        del C
+    del Bt_dev
     t0 = time.perf_counter()
     for r0 in range(0, M, ORACLE_CHUNK):
         r1 = min(M, r0 + ORACLE_CHUNK)
