@@ -50,7 +50,7 @@ typedef short shortx4 __attribute__((ext_vector_type(4)));
 // Sign-extended byte `byte` of word w as float (one v_cvt_f32_i32 with a byte select).
 ATB_DEV float mant_to_float(int w, int byte) { return (float)(int)(signed char)(w >> (8 * byte)); }
 
-template <int T_MA_, int T_MC_, int T_K_, int T_N_, int WM_, int WN_, int PF_, int AB_ = 2, int AO_ = -1, int BO_ = 0, int KU_ = 2, int NB_ = 2, int HW_ = 0>
+template <int T_MA_, int T_MC_, int T_K_, int T_N_, int WM_, int WN_, int PF_, int AB_ = 2, int AO_ = -1, int BO_ = 0, int KU_ = 2, int NB_ = 2, int HW_ = 0, bool ASWZ_ = false>
 struct Shape {
     static constexpr int T_MA = T_MA_, T_MC = T_MC_, T_K = T_K_, T_N = T_N_, WM = WM_, WN = WN_;
     static constexpr int PF = PF_;                // A sub-tiles fetched this many phases ahead of their use
@@ -85,14 +85,19 @@ struct Shape {
     static constexpr int KS = T_K / 16;           // MFMA k-slices per K-step
     static constexpr int PER = SMT / WM;          // bands of one sub-tile per wave row
     static constexpr int NM = PER * KS * NTW;     // MFMAs per wave per microkernel
-    // LDS pitches in bytes.  The pad de-phases the banks for the fragment reads.
-    static constexpr int PA = T_K * 2 + 16;
+    // LDS pitches in bytes.  The pad de-phases the banks for the fragment reads.  ASWZ: the A rows are not padded;
+    // the 16-byte chunks of a row are XOR-swizzled by (row / 2) mod 8 instead (sixteen consecutive rows then cover the
+    // 64 banks once, for the fragment reads and for the staging stores alike).  That saves 16 bytes per row, which is
+    // what lets the symmetric 256-row tile keep a third B buffer within the CU's 160 KiB.
+    static constexpr bool ASWZ = ASWZ_;
+    static constexpr int PBF = T_K * 2 + 16;      // pitch of a tile staged like A but always padded (B^T in BFP16)
+    static constexpr int PA = ASWZ ? T_K * 2 : PBF;
     static constexpr int PB = T_N * 2;            // B rows are not padded: an XOR swizzle of the 16-byte chunks avoids the bank conflicts
     static constexpr int A_BYTES = T_MA * PA;
     static constexpr int B_BYTES = T_K * PB;
     static constexpr int LDS_BYTES = AB * A_BYTES + NB * B_BYTES;
     // B given as BFP16 (B^T, N x K, blocks along K): the tile is staged like A, [n][k] with pitch PA
-    static constexpr int BT_BYTES = T_N * PA;
+    static constexpr int BT_BYTES = T_N * PBF;
     static constexpr int LDS_BYTES_BT = AB * A_BYTES + 2 * BT_BYTES;
     static constexpr int BT_SLABS = T_N * T_K / 16 / NTS;      // 16-mantissa chunks of the tile per staging thread
     // staging work per thread: A in chunks of ACE mantissas (ACE/8 BFP16 blocks), B in chunks of 8 bf16
@@ -112,6 +117,7 @@ struct Shape {
     static constexpr int SWZ = (T_N / 8 >= 16) ? 2 : 1;
     static constexpr int NBASE = (NTW < 4) ? NTW : 4;   // distinct per-lane read bases (the swizzle permutes 4 bands)
     static_assert(T_MC % T_MA == 0, "rho must be an integer");
+    static_assert(!ASWZ || (T_K == 64 && AB == 2 && HW == 0), "the A swizzle is written for rows of 8 chunks");
     static_assert(NB >= 2, "the B tile being multiplied and the one being fetched");
     static_assert(KU % 2 == 0 && PF >= 2 && (KU * RHO) % PF == 0, "prefetch distance: at least 2 (fetch and decode overlap), dividing the sub-tiles of one loop iteration");
     static_assert(AB == 2 || (AB == 4 && PF >= 3 && (KU * RHO) % 4 == 0), "4 A buffers need a fetch distance of 3 or more and must divide the sub-tiles of one loop iteration");
@@ -243,6 +249,8 @@ struct TileKernel {
     int b_t, b_n0, b_steps;            // B requests: likewise with the column origin
     // LDS byte addresses of this thread's staging writes and fragment reads, per buffer
     char *a_wr[S::AB], *b_wr[2];
+    const char *a_rdk[S::KS];          // ASWZ: this lane's fragment read address per k-slice, in A buffer 0, band 0
+    int a_w1;                          // ASWZ: byte offset (+16 or -16) of the second 16-byte piece of a staged chunk
     static constexpr int NRD = BTR ? S::KS : S::NBASE;
     const char *a_rd[S::AB], *b_rd[2][NRD];       // b_rd[buffer][column band mod 4]; transposed B: b_rd[buffer][k-slice]
     char *b_req[2];                    // LDS byte address of this wave's first 1 KiB B request, per buffer
@@ -300,9 +308,24 @@ struct TileKernel {
 #pragma unroll
         for (int b = 0; b < S::AB; ++b) {
             char *a_base = lds + b * S::A_BYTES;
-            a_wr[b] = a_base + (a_row + A_FIRST * (NTS / A_CPR)) * S::PA + a_q * (ACE * 2);
+            if constexpr (S::ASWZ) {
+                // chunk c of row r sits at position c ^ ((r / 2) % 8); a thread's rows are 64 apart, so one swizzle serves them all
+                const int row = a_row + A_FIRST * (NTS / A_CPR), swz = (row >> 1) & 7;
+                a_wr[b] = a_base + row * S::PA + (((a_q * (ACE / 8)) ^ swz) * 16);
+            } else {
+                a_wr[b] = a_base + (a_row + A_FIRST * (NTS / A_CPR)) * S::PA + a_q * (ACE * 2);
+            }
             // A fragment: lane l reads row l%32 of a band, k = ks*16 + 8*(l/32) .. +7
             a_rd[b] = a_base + (wm * 32 + (lane & 31)) * S::PA + (lane >> 5) * 16;
+        }
+        a_w1 = 16;
+        if constexpr (S::ASWZ) {
+            static_assert(!S::ASWZ || (ACE == 16 && !PAIRK), "swizzled A staging: chunks of two 16-byte pieces, one chunk per row and thread");
+            const int wrow = a_row + A_FIRST * (NTS / A_CPR);
+            a_w1 = (((wrow >> 1) & 1) != 0) ? -16 : 16;               // piece 2q+1 lands left of piece 2q where the swizzle is odd
+            const int rrow = wm * 32 + (lane & 31), rswz = (rrow >> 1) & 7;
+#pragma unroll
+            for (int ks = 0; ks < S::KS; ++ks) a_rdk[ks] = lds + rrow * S::PA + (((2 * ks + (lane >> 5)) ^ rswz) * 16);
         }
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
@@ -336,9 +359,9 @@ struct TileKernel {
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
                 char *b_base = lds + S::AB * S::A_BYTES + b * B_BYTES;
-                bt_wr[b] = b_base + b_row * S::PA + b_q * 32;
+                bt_wr[b] = b_base + b_row * S::PBF + b_q * 32;
                 // B fragment: lane l reads column (row of B^T) l%32 of a band, k = ks*16 + 8*(l/32) .. +7
-                bt_rd[b] = b_base + (wn * S::NTW * 32 + (lane & 31)) * S::PA + (lane >> 5) * 16;
+                bt_rd[b] = b_base + (wn * S::NTW * 32 + (lane & 31)) * S::PBF + (lane >> 5) * 16;
             }
             // rows >= N of B^T lie beyond the end of the planes and read as zero
 #pragma unroll
@@ -679,7 +702,8 @@ struct TileKernel {
             pk.v = bf16x2{(__bf16)ldf[(u - 2) % 2][0], (__bf16)ldf[(u - 2) % 2][1]};
             dec[t % 4] = pk.w;
             if constexpr (t % 4 == 3) {
-                char *dst = dst_base + ((!ISB && PAIRK) ? i * (ACE * 2) : i * ROWS * S::PA) + (t / 4) * 16;
+                char *dst = dst_base + ((!ISB && PAIRK) ? i * (ACE * 2) : i * ROWS * (ISB ? S::PBF : S::PA)) +
+                            ((!ISB && S::ASWZ) ? (t / 4) * a_w1 : (t / 4) * 16);
                 *reinterpret_cast<intx4 *>(dst) = intx4{(int)dec[0], (int)dec[1], (int)dec[2], (int)dec[3]};
             }
         }
@@ -762,7 +786,7 @@ struct TileKernel {
     ATB_DEV void read_b_frag(int buf)
     {
         if constexpr (BBFP) {
-            bfrag[ks][nt] = *reinterpret_cast<const bf16x8 *>(bt_rd[buf] + nt * 32 * S::PA + ks * 32);
+            bfrag[ks][nt] = *reinterpret_cast<const bf16x8 *>(bt_rd[buf] + nt * 32 * S::PBF + ks * 32);
         } else if constexpr (BTR) {
             const char *base = (S::NB > 2) ? b_rd[0][ks] + b_read_off : b_rd[buf][ks];
             bfrag[ks][nt] = *reinterpret_cast<const bf16x8 *>(base + nt * 32 * PBT);
@@ -791,17 +815,20 @@ struct TileKernel {
     // The fragments of consecutive bands (counted across sub-tiles) alternate between the two
     // halves of afrag: `par` is that running band index mod 2.
     template <int par, int il, int ks>
-    ATB_DEV void read_a_frag(const char *a_src)
+    ATB_DEV void read_a_frag(int buf)
     {
-        afrag[par][ks] = *reinterpret_cast<const bf16x8 *>(a_src + il * S::WM * 32 * S::PA + ks * 32);
+        if constexpr (S::ASWZ)       // the k-slice's chunk position depends on the row: one address per k-slice, buffer and band as constants
+            afrag[par][ks] = *reinterpret_cast<const bf16x8 *>(a_rdk[ks] + buf * S::A_BYTES + il * S::WM * 32 * S::PA);
+        else
+            afrag[par][ks] = *reinterpret_cast<const bf16x8 *>(a_rd[buf] + il * S::WM * 32 * S::PA + ks * 32);
     }
 
     template <int par, int ks = 0>
-    ATB_DEV void read_first_band(const char *a_src)
+    ATB_DEV void read_first_band(int buf)
     {
         if constexpr (ks < S::KS) {
-            read_a_frag<par, 0, ks>(a_src);
-            read_first_band<par, ks + 1>(a_src);
+            read_a_frag<par, 0, ks>(buf);
+            read_first_band<par, ks + 1>(buf);
         }
     }
 
@@ -876,9 +903,9 @@ struct TileKernel {
             side_range<ki, s, j0, j1>();
             if constexpr (nt == S::NTW - 1 && COMPUTE) {
                 if constexpr (il + 1 < S::PER)
-                    read_a_frag<par ^ 1, il + 1, ks>(a_rd[g % S::AB]);
+                    read_a_frag<par ^ 1, il + 1, ks>(g % S::AB);
                 else if constexpr (S::AB == 4)      // first band of the next sub-tile, already complete in LDS
-                    read_a_frag<par ^ 1, 0, ks>(a_rd[(g + 1) % S::AB]);
+                    read_a_frag<par ^ 1, 0, ks>((g + 1) % S::AB);
             }
             if constexpr (last_phase && il + 1 == S::PER && COMPUTE) read_b_frag<ks, nt>(kpar ^ 1);
             ATB_FENCE();
@@ -892,7 +919,7 @@ struct TileKernel {
     {
         if constexpr (s < S::RHO) {
             constexpr int g = ki * S::RHO + s;
-            if constexpr (S::AB == 2 && COMPUTE) read_first_band<(g * S::PER) % 2>(a_rd[g % 2]);
+            if constexpr (S::AB == 2 && COMPUTE) read_first_band<(g * S::PER) % 2>(g % 2);
             ATB_FENCE();
             slots<ki, s, 0>();
             // The B tile requested (straight into LDS) in the first phase of a K-step is read in the
@@ -977,7 +1004,7 @@ struct TileKernel {
         }
         // B buffer 0 is refilled from the first phase on: every wave must have its fragments first
         switch_barrier();
-        if constexpr (S::AB == 4 && COMPUTE) read_first_band<0>(a_rd[0]);
+        if constexpr (S::AB == 4 && COMPUTE) read_first_band<0>(0);
 
         // The number of K-steps is rounded up to a whole loop body: the extra steps multiply by B rows
         // >= K, which read as zero.  The last K-steps of a tile already request, decode and stage the
@@ -1224,6 +1251,13 @@ Instance make_instance(double eff_scale = 0.0, double lone_cap = 0.0)
 #ifndef ATB_ATB_B_RING
 #define ATB_ATB_B_RING 2
 #endif
+// The symmetric 256 x 256 tile can have a third B buffer too if its A rows give up their padding (Shape::ASWZ:
+// 64 + 96 KiB = exactly the CU's 160 KiB); a B tile then has two K-steps to arrive instead of one.  Measured on
+// 8192^3: -0.9 % (1260 against 1271 TFLOP/s, interleaved timing); the waves that await the B tile are not the ones
+// the K-step waits for.  Build option -DATB_SYM_B_RING=3; the library ships with 2.
+#ifndef ATB_SYM_B_RING
+#define ATB_SYM_B_RING 2
+#endif
 #ifndef ATB_ATB_A_RING
 #define ATB_ATB_A_RING 2
 #endif
@@ -1240,7 +1274,7 @@ const Instance g_instances[] = {
     // The A fetch runs one to one and a half K-steps ahead of its use at every rho (PF phases).
     // These three, and the mid-size and small tiles below, also come with B and/or C stored as BFP16
     // (the all-BFP16 configurations of Sec. 6.1); the 4-wave 256-row instances have no registers left for it.
-    make_instance<Shape<256, 256, 64, 256, 2, 4, 2, 2, 4, 0>, true>(1.0),
+    make_instance<Shape<256, 256, 64, 256, 2, 4, 2, 2, 4, 0, 2, ATB_SYM_B_RING, 0, (ATB_SYM_B_RING == 3)>, true>(1.0),
     // What ATB's smaller A buffers free in LDS (36 KiB at rho = 2, 54 KiB at rho = 4) could hold a third B buffer
     // (ATB_ATB_B_RING = 3: 132 / 114 KiB; the symmetric tile cannot have one, 72 + 96 KiB) or a ring of four A
     // buffers whose decode runs two sub-tiles ahead, so that a microkernel's first fragments are read before the
