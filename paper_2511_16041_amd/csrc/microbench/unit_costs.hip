@@ -197,6 +197,73 @@ void run_mix(float *out, int iters, const char *what)
     printf("mix_kernel<%2d>   %-62s %6.2f ns per MFMA per SIMD = %.0f TFLOP/s\n", F, what, x, 32768.0 * 1024 / x / 1e3);
 }
 
+// Issue cost of single VALU instructions next to MFMAs: every wave (two per SIMD) issues one MFMA and then N copies
+// of one instruction per slot; the difference between N = 16 and N = 8 is what 8 instructions cost.
+template <int KIND> __device__ __forceinline__ void one_op(unsigned &x, unsigned y, float &f, float g)
+{
+    if (KIND == 0) asm volatile("v_add_u32_e32 %0, %1, %0" : "+v"(x) : "v"(y));
+    if (KIND == 1) asm volatile("v_cvt_f32_i32_sdwa %0, sext(%1) dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1" : "=v"(f) : "v"(y));
+    if (KIND == 2) asm volatile("v_cvt_f32_ubyte1_e32 %0, %1" : "=v"(f) : "v"(y));
+    if (KIND == 3) asm volatile("v_ldexp_f32 %0, %1, %2" : "=v"(f) : "v"(g), "v"(y));
+    if (KIND == 4) asm volatile("v_mul_f32_e32 %0, %1, %0" : "+v"(f) : "v"(g));
+    if (KIND == 5) asm volatile("v_fma_f32 %0, %1, %2, %2" : "=v"(f) : "v"(g), "v"(g));
+    if (KIND == 6) asm volatile("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(x) : "v"(f), "v"(g));
+    if (KIND == 7) asm volatile("v_perm_b32 %0, %1, %2, %3" : "=v"(x) : "v"(y), "v"(x), "v"(y));
+    if (KIND == 8) asm volatile("v_pk_add_u16 %0, %1, %0" : "+v"(x) : "v"(y));
+    if (KIND == 9) asm volatile("v_bfe_u32 %0, %1, 8, 8" : "=v"(x) : "v"(y));
+}
+
+template <int KIND, int N>
+__global__ void __launch_bounds__(kThreads) op_kernel(float *out, int iters, int seed)
+{
+    bf16x8 a, b;
+    for (int t = 0; t < 8; ++t) { a[t] = (__bf16)(float)(threadIdx.x % 3); b[t] = (__bf16)(float)(threadIdx.x % 5); }
+    floatx16 acc[8];
+    for (int i = 0; i < 8; ++i) for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    unsigned x[4] = {1u + seed, 2u, 3u, 4u};
+    float f[4] = {1.f, 2.f, 3.f, 4.f};
+    unsigned y = seed + threadIdx.x;
+    float g = 1.5f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+            FENCE();
+#pragma unroll
+            for (int v = 0; v < N; ++v) one_op<KIND>(x[v & 3], y, f[v & 3], g);
+            FENCE();
+        }
+    }
+    float s = 0;
+    for (int i = 0; i < 8; ++i) for (int q = 0; q < 16; ++q) s += acc[i][q];
+    out[blockIdx.x * kThreads + threadIdx.x] = s + x[0] + x[1] + x[2] + x[3] + f[0] + f[1] + f[2] + f[3];
+}
+
+template <int KIND, int N>
+double run_op(float *out)     // nanoseconds per MFMA per SIMD
+{
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
+    const int iters = 4000;
+    hipLaunchKernelGGL((op_kernel<KIND, N>), dim3(kBlocks), dim3(kThreads), 0, 0, out, 10, 1);
+    CK(hipDeviceSynchronize());
+    CK(hipEventRecord(e0));
+    hipLaunchKernelGGL((op_kernel<KIND, N>), dim3(kBlocks), dim3(kThreads), 0, 0, out, iters, 1);
+    CK(hipEventRecord(e1));
+    CK(hipEventSynchronize(e1));
+    float ms;
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    return ms * 1e6 / (iters * 16.0);
+}
+
+template <int KIND>
+void op_cost(float *out, const char *name)
+{
+    const double a = run_op<KIND, 8>(out), b = run_op<KIND, 16>(out);
+    printf("op_kernel  %-26s  MFMA + 8: %6.2f ns   MFMA + 16: %6.2f ns   => %.2f ns per instruction, %.1f ns for the MFMA alone\n",
+           name, a, b, (b - a) / 8.0, a - (b - a));
+}
+
 int main()
 {
     float *out;
@@ -223,5 +290,16 @@ int main()
     run_mix<7>(out, 700000, "+ half a BFP16 decode pair per MFMA (waves 0-3)");
     run_mix<15>(out, 700000, "+ LDS stores of the decoded A (waves 0-3)");
     run_mix<5>(out, 700000, "register operands + the decode, no LDS");
+    // single VALU instructions next to MFMAs (constant operands: the clock stays near its maximum)
+    op_cost<0>(out, "v_add_u32");
+    op_cost<1>(out, "v_cvt_f32_i32 (byte select)");
+    op_cost<2>(out, "v_cvt_f32_ubyte1");
+    op_cost<3>(out, "v_ldexp_f32");
+    op_cost<4>(out, "v_mul_f32");
+    op_cost<5>(out, "v_fma_f32");
+    op_cost<6>(out, "v_cvt_pk_bf16_f32");
+    op_cost<7>(out, "v_perm_b32");
+    op_cost<8>(out, "v_pk_add_u16");
+    op_cost<9>(out, "v_bfe_u32");
     return 0;
 }
