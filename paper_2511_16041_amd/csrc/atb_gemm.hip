@@ -50,7 +50,7 @@ typedef short shortx4 __attribute__((ext_vector_type(4)));
 // Sign-extended byte `byte` of word w as float (one v_cvt_f32_i32 with a byte select).
 ATB_DEV float mant_to_float(int w, int byte) { return (float)(int)(signed char)(w >> (8 * byte)); }
 
-template <int T_MA_, int T_MC_, int T_K_, int T_N_, int WM_, int WN_, int PF_, int AB_ = 2, int AO_ = -1, int BO_ = 0, int KU_ = 2, int NB_ = 2, int HW_ = 0, bool ASWZ_ = false>
+template <int T_MA_, int T_MC_, int T_K_, int T_N_, int WM_, int WN_, int PF_, int AB_ = 2, int AO_ = -1, int BO_ = 0, int KU_ = 2, int NB_ = 2, int HW_ = 0, bool ASWZ_ = false, int SKEW_ = 0>
 struct Shape {
     static constexpr int T_MA = T_MA_, T_MC = T_MC_, T_K = T_K_, T_N = T_N_, WM = WM_, WN = WN_;
     static constexpr int PF = PF_;                // A sub-tiles fetched this many phases ahead of their use
@@ -90,6 +90,11 @@ struct Shape {
     // 64 banks once, for the fragment reads and for the staging stores alike).  That saves 16 bytes per row, which is
     // what lets the symmetric 256-row tile keep a third B buffer within the CU's 160 KiB.
     static constexpr bool ASWZ = ASWZ_;
+    // Uneven deal of the C tile's 32-row bands between the two wave groups of an 8-wave workgroup: the group that
+    // decodes A (waves 0-3) multiplies SKEW bands fewer per C tile than its even share and the other group SKEW more,
+    // so that the decoding waves' longer instruction stream and the other waves' shorter one end a phase together.
+    // The wave grid is then laid out with the wave row equal to the group (see TileKernel).
+    static constexpr int SKEW = SKEW_;
     static constexpr int PBF = T_K * 2 + 16;      // pitch of a tile staged like A but always padded (B^T in BFP16)
     static constexpr int PA = ASWZ ? T_K * 2 : PBF;
     static constexpr int PB = T_N * 2;            // B rows are not padded: an XOR swizzle of the 16-byte chunks avoids the bank conflicts
@@ -129,7 +134,8 @@ struct Shape {
     static_assert(AO >= 0 && AO <= A_SLABS && BO >= 0 && BO <= B_SLABS, "staging split");
     static_assert(B_CPR >= 8, "the B swizzle needs 8 chunks per row");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
-    static_assert(MTW * NTW * 16 <= 256, "C tile must fit the accumulator registers");
+    static_assert((MTW + SKEW) * NTW * 16 <= 256, "C tile must fit the accumulator registers");
+    static_assert(SKEW == 0 || (CW == 8 && WM == 2 && HW == 0 && AB == 2 && SKEW < MTW), "the uneven deal is between the two wave groups of a 2 x 4 grid");
 };
 
 typedef int intx4 __attribute__((ext_vector_type(4)));
@@ -165,6 +171,19 @@ ATB_DEV bool tile_origin(const GemmParams &p, int t, int &tm0, int &tn0)
     tn0 = (in_band / rows_here) * S::T_N;
     return true;
 }
+
+// Bands of the C tile per wave.  Even deal: band il * WM + wm of every sub-tile, PER per sub-tile.  Uneven deal
+// (Shape::SKEW, only where the first wave group decodes and the second does not): the first group's waves form wave
+// row 0 and take the first per(s) bands of sub-tile s, the second group's the rest.
+template <class S, int ROLE, bool VEC, bool BBFP>
+struct BandDeal {
+    static constexpr bool SKEWED = S::SKEW > 0 && (ROLE == 1 || ROLE == 2) && VEC && !BBFP;   // (the odd-N path has no registers to spare for it)
+    static constexpr int moved(int s) { return SKEWED ? (S::SKEW * (s + 1)) / S::RHO - (S::SKEW * s) / S::RHO : 0; }   // bands of sub-tile s that change hands
+    static constexpr int per(int s) { return ROLE == 1 ? S::PER - moved(s) : ROLE == 2 ? S::PER + moved(s) : S::PER; }
+    static constexpr int first_local(int s) { int n = 0; for (int t = 0; t < s; ++t) n += per(t); return n; }         // accumulator band of the wave's first band of sub-tile s
+    // band of sub-tile s that this wave's il-th band is, not counting the wave row's own offset in the even deal
+    static constexpr int band(int s, int il) { return SKEWED ? (ROLE == 1 ? il : S::PER - moved(s) + il) : il * S::WM; }
+};
 
 // The per-workgroup state of one C tile.  Everything is indexed with compile-time constants after
 // inlining, so the arrays live in registers (acc in AccVGPRs).
@@ -236,6 +255,14 @@ struct TileKernel {
     static_assert((ROLE == 0) == (S::CW != 8 && S::HW == 0) && (ROLE >= 3) == (S::HW > 0), "two staging groups exactly when two waves share a SIMD; helper roles exactly with helper waves");
     static_assert(!BTR || (VEC && !BBFP && !SK && S::T_K == 64), "the transposed-B path: bf16 B^T, K-steps of 64 (8 chunks per LDS row, swizzled over 8 row pairs)");
     static constexpr int PBT = S::T_K * 2;                                                // LDS pitch of a B^T tile row
+    typedef BandDeal<S, ROLE, VEC, BBFP> D;
+    static constexpr bool SKEWED = D::SKEWED;
+    static constexpr int MTW = D::first_local(S::RHO);                                    // accumulator bands of this wave
+    static constexpr int per(int s) { return D::per(s); }
+    static constexpr int first_local(int s) { return D::first_local(s); }
+    static constexpr int band(int s, int il) { return D::band(s, il); }
+    static constexpr int nm(int s) { return D::per(s) * S::KS * S::NTW; }                 // MFMAs of this wave in phase s
+    static constexpr int bands_before(int g) { return (g / S::RHO) * MTW + D::first_local(g % S::RHO); }   // running band count at sub-tile g of the loop body
 
     const GemmParams &p;
     Rsrc rs;
@@ -277,7 +304,7 @@ struct TileKernel {
     intx4 bt_mant[2][BTPTN];
     unsigned bt_expo[2][BTPTN];
 
-    floatx16 acc[S::MTW][S::NTW];
+    floatx16 acc[MTW][S::NTW];
     bf16x8 bfrag[S::KS][S::NTW];       // this wave's slice of the resident B tile
     bf16x8 afrag[2][S::KS];            // A fragments of the current and the next band
     intx4 a_mant[S::PF][APTN];
@@ -293,8 +320,13 @@ struct TileKernel {
         tid = threadIdx.x;
         lane = tid & 63;
         const int wave = tid >> 6;
-        wm = wave % S::WM;
-        wn = wave / S::WM;
+        if constexpr (SKEWED) {      // wave row = wave group; wm only places the fragment reads and the stores, where the band carries the row
+            wm = 0;
+            wn = wave % S::WN;
+        } else {
+            wm = wave % S::WM;
+            wn = wave / S::WM;
+        }
         const int stid = tid % NTS;                  // index within the threads that share this staging job
         const int a_row = PAIRK ? stid / 2 : stid / A_CPR;
         const int a_q = PAIRK ? 2 * (stid % 2) : stid % A_CPR;           // first chunk of this thread in its row
@@ -405,7 +437,7 @@ struct TileKernel {
             }
         }
 #pragma unroll
-        for (int a = 0; a < S::MTW; ++a)
+        for (int a = 0; a < MTW; ++a)
 #pragma unroll
             for (int b = 0; b < S::NTW; ++b)
 #pragma unroll
@@ -810,25 +842,25 @@ struct TileKernel {
         }
     }
 
-    // A fragment (band il of the sub-tile, k-slice ks).  Bands of the C tile are dealt round-robin
-    // to the wave rows: this wave reads band il*WM + wm of the sub-tile.
+    // A fragment (band bd of the sub-tile as band(s, il) gives it, k-slice ks).  In the even deal the bands of the
+    // C tile go round-robin to the wave rows: this wave reads band il*WM + wm of the sub-tile (wm is in a_rd).
     // The fragments of consecutive bands (counted across sub-tiles) alternate between the two
     // halves of afrag: `par` is that running band index mod 2.
-    template <int par, int il, int ks>
+    template <int par, int bd, int ks>
     ATB_DEV void read_a_frag(int buf)
     {
         if constexpr (S::ASWZ)       // the k-slice's chunk position depends on the row: one address per k-slice, buffer and band as constants
-            afrag[par][ks] = *reinterpret_cast<const bf16x8 *>(a_rdk[ks] + buf * S::A_BYTES + il * S::WM * 32 * S::PA);
+            afrag[par][ks] = *reinterpret_cast<const bf16x8 *>(a_rdk[ks] + buf * S::A_BYTES + bd * 32 * S::PA);
         else
-            afrag[par][ks] = *reinterpret_cast<const bf16x8 *>(a_rd[buf] + il * S::WM * 32 * S::PA + ks * 32);
+            afrag[par][ks] = *reinterpret_cast<const bf16x8 *>(a_rd[buf] + bd * 32 * S::PA + ks * 32);
     }
 
-    template <int par, int ks = 0>
+    template <int par, int s, int ks = 0>
     ATB_DEV void read_first_band(int buf)
     {
         if constexpr (ks < S::KS) {
-            read_a_frag<par, 0, ks>(buf);
-            read_first_band<par, ks + 1>(buf);
+            read_a_frag<par, band(s, 0), ks>(buf);
+            read_first_band<par, s, ks + 1>(buf);
         }
     }
 
@@ -883,31 +915,31 @@ struct TileKernel {
     template <int ki, int s, int m>
     ATB_DEV void slots()
     {
-        if constexpr (m < S::NM) {
+        if constexpr (m < nm(s)) {
             constexpr int kpar = ki & 1;
             constexpr int il = m / (S::KS * S::NTW), ks = (m / S::NTW) % S::KS, nt = m % S::NTW;
-            constexpr int local = (s * S::SMT) / S::WM + il;      // accumulator band of this wave
+            constexpr int local = first_local(s) + il;            // accumulator band of this wave
             constexpr bool last_phase = (s + 1 == S::RHO);
             constexpr int nside = n_side<s>();
             constexpr int g = ki * S::RHO + s;
-            constexpr int par = (g * S::PER + il) % 2;            // which half of afrag this band uses
+            constexpr int par = (bands_before(g) + il) % 2;       // which half of afrag this band uses
             if constexpr (COMPUTE)
                 acc[local][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag[ks][nt], afrag[par][ks],
                                                                         acc[local][nt], 0, 0, 0);
             ATB_FENCE();
             // the last eighth of the slots carries no side work, so that the LDS stores of the decode
             // have drained when the wave reaches the switch barrier
-            constexpr int NS = S::NM - S::NM / 8;
+            constexpr int NS = nm(s) - nm(s) / 8;
             constexpr int j0 = (m * nside) / NS < nside ? (m * nside) / NS : nside;
             constexpr int j1 = ((m + 1) * nside) / NS < nside ? ((m + 1) * nside) / NS : nside;
             side_range<ki, s, j0, j1>();
             if constexpr (nt == S::NTW - 1 && COMPUTE) {
-                if constexpr (il + 1 < S::PER)
-                    read_a_frag<par ^ 1, il + 1, ks>(g % S::AB);
+                if constexpr (il + 1 < per(s))
+                    read_a_frag<par ^ 1, band(s, il + 1), ks>(g % S::AB);
                 else if constexpr (S::AB == 4)      // first band of the next sub-tile, already complete in LDS
-                    read_a_frag<par ^ 1, 0, ks>((g + 1) % S::AB);
+                    read_a_frag<par ^ 1, band((s + 1) % S::RHO, 0), ks>((g + 1) % S::AB);
             }
-            if constexpr (last_phase && il + 1 == S::PER && COMPUTE) read_b_frag<ks, nt>(kpar ^ 1);
+            if constexpr (last_phase && il + 1 == per(s) && COMPUTE) read_b_frag<ks, nt>(kpar ^ 1);
             ATB_FENCE();
             slots<ki, s, m + 1>();
         }
@@ -919,7 +951,7 @@ struct TileKernel {
     {
         if constexpr (s < S::RHO) {
             constexpr int g = ki * S::RHO + s;
-            if constexpr (S::AB == 2 && COMPUTE) read_first_band<(g * S::PER) % 2>(g % 2);
+            if constexpr (S::AB == 2 && COMPUTE) read_first_band<bands_before(g) % 2, s>(g % 2);
             ATB_FENCE();
             slots<ki, s, 0>();
             // The B tile requested (straight into LDS) in the first phase of a K-step is read in the
@@ -1004,7 +1036,7 @@ struct TileKernel {
         }
         // B buffer 0 is refilled from the first phase on: every wave must have its fragments first
         switch_barrier();
-        if constexpr (S::AB == 4 && COMPUTE) read_first_band<0>(0);
+        if constexpr (S::AB == 4 && COMPUTE) read_first_band<0, 0>(0);
 
         // The number of K-steps is rounded up to a whole loop body: the extra steps multiply by B rows
         // >= K, which read as zero.  The last K-steps of a tile already request, decode and stage the
@@ -1016,7 +1048,7 @@ struct TileKernel {
             c_t += t_stride;
             if (!tile_at(c_t, m0, n0)) break;
 #pragma unroll
-            for (int a = 0; a < S::MTW; ++a)
+            for (int a = 0; a < MTW; ++a)
 #pragma unroll
                 for (int b = 0; b < S::NTW; ++b)
 #pragma unroll
@@ -1026,14 +1058,22 @@ struct TileKernel {
         wait_vm<0>();
     }
 
+    // 32-row band of the C tile that accumulator band a of this wave holds (without the wave row's offset wm of the even deal)
+    static constexpr int band_of_acc(int a)
+    {
+        int s = 0;
+        while (s + 1 < S::RHO && first_local(s + 1) <= a) ++s;
+        return s * S::SMT + band(s, a - first_local(s));
+    }
+
     // epilogue: fp32 -> bf16 (round to nearest even) and store, once per tile.  Lane l of band
     // (a, b) holds row l%32 and columns 8*g + 4*(l/32) + 0..3 for g = 0..3.
     ATB_DEV void store_c()
     {
         const bool st_vec = (p.N % 4) == 0;
 #pragma unroll
-        for (int a = 0; a < S::MTW; ++a) {
-            const int m = m0 + (a * S::WM + wm) * 32 + (lane & 31);
+        for (int a = 0; a < MTW; ++a) {
+            const int m = m0 + (band_of_acc(a) + wm) * 32 + (lane & 31);
 #pragma unroll
             for (int b = 0; b < S::NTW; ++b) {
                 const int nb = n0 + (wn * S::NTW + b) * 32 + 4 * (lane >> 5);
@@ -1067,8 +1107,8 @@ struct TileKernel {
     ATB_DEV void store_c_bfp()
     {
 #pragma unroll
-        for (int a = 0; a < S::MTW; ++a) {
-            const int m = m0 + (a * S::WM + wm) * 32 + (lane & 31);
+        for (int a = 0; a < MTW; ++a) {
+            const int m = m0 + (band_of_acc(a) + wm) * 32 + (lane & 31);
 #pragma unroll
             for (int b = 0; b < S::NTW; ++b) {
                 const int nb = n0 + (wn * S::NTW + b) * 32 + 4 * (lane >> 5);
@@ -1261,6 +1301,13 @@ Instance make_instance(double eff_scale = 0.0, double lone_cap = 0.0)
 #ifndef ATB_ATB_A_RING
 #define ATB_ATB_A_RING 2
 #endif
+// Bands of the 256-row C tile that move from the decoding wave group to the other one (Shape::SKEW).
+#ifndef ATB_SYM_SKEW
+#define ATB_SYM_SKEW 0
+#endif
+#ifndef ATB_ATB_SKEW
+#define ATB_ATB_SKEW 0
+#endif
 
 const Instance g_instances[] = {
 #if ATB_IN_GROUP(0)
@@ -1274,7 +1321,7 @@ const Instance g_instances[] = {
     // The A fetch runs one to one and a half K-steps ahead of its use at every rho (PF phases).
     // These three, and the mid-size and small tiles below, also come with B and/or C stored as BFP16
     // (the all-BFP16 configurations of Sec. 6.1); the 4-wave 256-row instances have no registers left for it.
-    make_instance<Shape<256, 256, 64, 256, 2, 4, 2, 2, 4, 0, 2, ATB_SYM_B_RING, 0, (ATB_SYM_B_RING == 3)>, true>(1.0),
+    make_instance<Shape<256, 256, 64, 256, 2, 4, 2, 2, 4, 0, 2, ATB_SYM_B_RING, 0, (ATB_SYM_B_RING == 3), ATB_SYM_SKEW>, true>(1.0),
     // What ATB's smaller A buffers free in LDS (36 KiB at rho = 2, 54 KiB at rho = 4) could hold a third B buffer
     // (ATB_ATB_B_RING = 3: 132 / 114 KiB; the symmetric tile cannot have one, 72 + 96 KiB) or a ring of four A
     // buffers whose decode runs two sub-tiles ahead, so that a microkernel's first fragments are read before the
@@ -1282,7 +1329,7 @@ const Instance g_instances[] = {
     // A ring: -3.8 % / -1.6 % at rho = 2 / 4): B tiles already arrive two K-steps after their request, and the
     // deeper A ring costs registers.  Both stay build options (-DATB_ATB_B_RING=3, -DATB_ATB_A_RING=4) for that
     // measurement; the library ships with 2 and 2.
-    make_instance<Shape<128, 256, 64, 256, 2, 4, (ATB_ATB_A_RING == 4 ? 4 : 2), ATB_ATB_A_RING, 2, 0, 2, ATB_ATB_B_RING>, true>(1.0),
+    make_instance<Shape<128, 256, 64, 256, 2, 4, (ATB_ATB_A_RING == 4 ? 4 : 2), ATB_ATB_A_RING, 2, 0, 2, ATB_ATB_B_RING, 0, false, ATB_ATB_SKEW>, true>(1.0),
     make_instance<Shape<64, 256, 64, 256, 2, 4, 4, ATB_ATB_A_RING, 1, 0, 2, ATB_ATB_B_RING>, true>(1.0),
     make_instance<Shape<32, 256, 64, 256, 1, 4, 8, 4>>(1.0),
     // T_K = 128 exists only with ATB: at rho = 8 the A buffers take 17 KiB next to 128 KiB of B; the
