@@ -26,12 +26,11 @@
 // B may also arrive as BFP16 (as B^T, blocks along K) and C may be written as BFP16 (Sec. 6.1's
 // all-BFP16 storage); see the BBFP / CBFP template flags of TileKernel.
 //
-// MFMA: v_mfma_f32_32x32x16_bf16.  Operand lane layout: lane l supplies row
-// (l % 32) of its operand and the 8 consecutive k values 8*(l/32) .. +7, which
-// for the A operand is exactly one BFP16 block.  The B fragment is passed as
-// the first operand and the A fragment as the second, so a lane of the result
-// holds one row m (= l % 32) and 16 columns n = 8*(v/4) + 4*(l/32) + v%4,
-// i.e. groups of 4 consecutive columns -> 8-byte bf16 stores.
+// MFMA: v_mfma_f32_16x16x32_bf16 or v_mfma_f32_32x32x16_bf16 (Shape::MB = 16 or 32 says which and why).
+// Operand lane layout: lane l supplies row (l % MB) of its operand and the 8 consecutive k values
+// 8*(l/MB) .. +7, which for the A operand is exactly one BFP16 block.  The B fragment is passed as
+// the first operand and the A fragment as the second, so a lane of the result holds one row m
+// (= l % MB) and groups of 4 consecutive columns (n = 8*g + 4*(l/MB) + 0..3) -> 8-byte bf16 stores.
 #include <algorithm>
 #include <mutex>
 
@@ -42,6 +41,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 
@@ -50,7 +50,7 @@ typedef short shortx4 __attribute__((ext_vector_type(4)));
 // Sign-extended byte `byte` of word w as float (one v_cvt_f32_i32 with a byte select).
 ATB_DEV float mant_to_float(int w, int byte) { return (float)(int)(signed char)(w >> (8 * byte)); }
 
-template <int T_MA_, int T_MC_, int T_K_, int T_N_, int WM_, int WN_, int PF_, int AB_ = 2, int AO_ = -1, int BO_ = 0, int KU_ = 2, int NB_ = 2, int HW_ = 0, bool ASWZ_ = false, int SKEW_ = 0>
+template <int T_MA_, int T_MC_, int T_K_, int T_N_, int WM_, int WN_, int PF_, int AB_ = 2, int AO_ = -1, int BO_ = 0, int KU_ = 2, int NB_ = 2, int HW_ = 0, bool ASWZ_ = false, int SKEW_ = 0, int MB_ = 0>
 struct Shape {
     static constexpr int T_MA = T_MA_, T_MC = T_MC_, T_K = T_K_, T_N = T_N_, WM = WM_, WN = WN_;
     static constexpr int PF = PF_;                // A sub-tiles fetched this many phases ahead of their use
@@ -82,9 +82,21 @@ struct Shape {
     static constexpr int SMT = T_MA / 32;         // bands per A sub-tile
     static constexpr int MTW = MT / WM;           // bands per wave
     static constexpr int NTW = T_N / 32 / WN;     // 32-column bands per wave
-    static constexpr int KS = T_K / 16;           // MFMA k-slices per K-step
+    // The MFMA.  gfx950 has two bf16 forms of the same peak rate: 32 x 32 x 16 (rows x columns x k per instruction)
+    // and 16 x 16 x 32.  The first needs half as many operand registers and instructions per flop; the second is the
+    // cheaper one in power, and this chip is power-limited: an MFMA-only loop on random bf16 operands sustains
+    // 1.92 PFLOP/s with 16 x 16 x 32 against 1.72 with 32 x 32 x 16.  MB = 16 where two waves of the workgroup share a
+    // SIMD (the other wave's instructions fill the gaps between the short MFMAs: +2-3 % on 8192^3), MB = 32 where a
+    // SIMD has one multiplying wave per workgroup, whose single instruction stream cannot issue twice as many MFMAs
+    // and their operand reads without gaps (measured 10-20 % slower with MB = 16), unless the instance says otherwise.
+    // A 32-row band of A is HB row blocks of MB rows.
+    static constexpr int MB = MB_ ? MB_ : (WM * WN == 8 ? 16 : 32);
+    static constexpr int KM = 512 / MB;           // k per MFMA
+    static constexpr int HB = 32 / MB;            // row blocks per band
+    static constexpr int NC = T_N / MB / WN;      // column blocks per wave
+    static constexpr int KS = T_K / KM;           // MFMA k-slices per K-step
+    static constexpr int ACC = MB * MB / 64;      // accumulator registers per block
     static constexpr int PER = SMT / WM;          // bands of one sub-tile per wave row
-    static constexpr int NM = PER * KS * NTW;     // MFMAs per wave per microkernel
     // LDS pitches in bytes.  The pad de-phases the banks for the fragment reads.  ASWZ: the A rows are not padded;
     // the 16-byte chunks of a row are XOR-swizzled by (row / 2) mod 8 instead (sixteen consecutive rows then cover the
     // 64 banks once, for the fragment reads and for the staging stores alike).  That saves 16 bytes per row, which is
@@ -115,26 +127,38 @@ struct Shape {
     static constexpr int B_SLABS = B_CHUNKS / NTS;
     static constexpr int BO = BO_;                          // ... and the second all of B
     static constexpr int B_CPR = T_N / 8;         // 16-byte chunks per B row
-    // B swizzle: chunk c of row k sits at chunk position c ^ ((k & 3) << SWZ) of its row.  A
-    // transposing read touches, per 32 lanes, 4 rows x 2 neighbouring 32-byte pieces; with SWZ = 2
-    // these 8 pieces cover 256 consecutive bytes, i.e. every LDS bank once.  Narrow tiles (fewer than
-    // 16 chunks per row) can only afford SWZ = 1, which keeps 16 lanes conflict-free.
-    static constexpr int SWZ = (T_N / 8 >= 16) ? 2 : 1;
-    static constexpr int NBASE = (NTW < 4) ? NTW : 4;   // distinct per-lane read bases (the swizzle permutes 4 bands)
+    // B swizzle: chunk c of row k sits at chunk position c ^ b_swz(k) of its row, so that the pieces of different
+    // rows that one transposing read touches fall into different LDS banks.
+    // MB = 32: per 32 lanes, 4 rows x 2 neighbouring 32-byte pieces; k mod 4 goes into bits 2-3 of the position and the
+    // 8 pieces cover 256 consecutive bytes, i.e. every bank once.  Narrow tiles (rows of 8 chunks) can only afford
+    // bits 1-2, which keeps 16 lanes conflict-free.
+    // MB = 16: per 32 lanes, the rows k0 .. k0+3 and k0+8 .. k0+11 of one 16-column block, 32 bytes of each.  Rows
+    // of 16 or more chunks (a multiple of 256 bytes, so all rows start in the same bank): bits 2-3 of the position
+    // from k mod 4, bit 1 from bit 3 of k.  Rows of 8 chunks (128 bytes: odd rows start half way round the banks,
+    // which separates k and k+1): bit 1 from bit 1 of k, bit 2 from bit 3 of k.
+    static constexpr bool WIDE = (T_N / 8 >= 16);
+    static constexpr int b_swz(int k)
+    {
+        if (MB == 32) return (k & 3) << (WIDE ? 2 : 1);
+        return WIDE ? (((k & 3) << 2) | (((k >> 3) & 1) << 1)) : ((((k >> 1) & 1) << 1) | (((k >> 3) & 1) << 2));
+    }
+    static constexpr int NBASE = (NC < 4) ? NC : 4;     // distinct per-lane read bases: the swizzle permutes groups of four column blocks
+    static_assert(MB == 32 || NC <= 4, "MB = 16: the B swizzle permutes the wave's (at most four) column blocks");
     static_assert(T_MC % T_MA == 0, "rho must be an integer");
     static_assert(!ASWZ || (T_K == 64 && AB == 2 && HW == 0), "the A swizzle is written for rows of 8 chunks");
     static_assert(NB >= 2, "the B tile being multiplied and the one being fetched");
     static_assert(KU % 2 == 0 && PF >= 2 && (KU * RHO) % PF == 0, "prefetch distance: at least 2 (fetch and decode overlap), dividing the sub-tiles of one loop iteration");
     static_assert(AB == 2 || (AB == 4 && PF >= 3 && (KU * RHO) % 4 == 0), "4 A buffers need a fetch distance of 3 or more and must divide the sub-tiles of one loop iteration");
     static_assert(T_K % 64 == 0, "a K-step is a whole number of 64-wide panels of the BFP16 layout");
-    static_assert(T_MA % 32 == 0 && T_N % (32 * WN) == 0 && T_K % 16 == 0, "MFMA 32x32x16 granularity");
+    static_assert(MB == 16 || MB == 32, "v_mfma_f32_16x16x32_bf16 or v_mfma_f32_32x32x16_bf16");
+    static_assert(T_MA % 32 == 0 && T_N % (32 * WN) == 0 && T_K % 32 == 0, "bands of 32 rows and columns, MFMA k-slices of 16 or 32");
     static_assert(MT % WM == 0 && SMT % WM == 0, "every sub-tile must feed every wave row equally");
     static_assert(A_CHUNKS % NTS == 0 && NTS % A_CPR == 0, "A staging must split evenly over the threads");
     static_assert(B_CHUNKS % NTS == 0 && NTS % B_CPR == 0, "B staging must split evenly over the threads");
     static_assert(AO >= 0 && AO <= A_SLABS && BO >= 0 && BO <= B_SLABS, "staging split");
     static_assert(B_CPR >= 8, "the B swizzle needs 8 chunks per row");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
-    static_assert((MTW + SKEW) * NTW * 16 <= 256, "C tile must fit the accumulator registers");
+    static_assert((MTW + SKEW) * HB * NC * ACC <= 256, "C tile must fit the accumulator registers");
     static_assert(SKEW == 0 || (CW == 8 && WM == 2 && HW == 0 && AB == 2 && SKEW < MTW), "the uneven deal is between the two wave groups of a 2 x 4 grid");
 };
 
@@ -152,6 +176,11 @@ struct Rsrc {
 constexpr int kRsrcFlags = 0x00020000;           // raw buffer, 32-bit data format
 
 #define ATB_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// MFMAs issued back to back per slot of the hand-made pipeline (see TileKernel::slots)
+#ifndef ATB_MFMA_GROUP
+#define ATB_MFMA_GROUP 1
+#endif
 
 // Origin of the t-th tile of this workgroup's XCD (false past the end of the walk).  Workgroups
 // are dealt round-robin to the 8 XCDs (each with its own L2); XCD x owns the contiguous run of
@@ -261,7 +290,7 @@ struct TileKernel {
     static constexpr int per(int s) { return D::per(s); }
     static constexpr int first_local(int s) { return D::first_local(s); }
     static constexpr int band(int s, int il) { return D::band(s, il); }
-    static constexpr int nm(int s) { return D::per(s) * S::KS * S::NTW; }                 // MFMAs of this wave in phase s
+    static constexpr int nm(int s) { return D::per(s) * S::HB * S::KS * S::NC; }              // MFMAs of this wave in phase s
     static constexpr int bands_before(int g) { return (g / S::RHO) * MTW + D::first_local(g % S::RHO); }   // running band count at sub-tile g of the loop body
 
     const GemmParams &p;
@@ -304,9 +333,10 @@ struct TileKernel {
     intx4 bt_mant[2][BTPTN];
     unsigned bt_expo[2][BTPTN];
 
-    floatx16 acc[MTW][S::NTW];
-    bf16x8 bfrag[S::KS][S::NTW];       // this wave's slice of the resident B tile
-    bf16x8 afrag[2][S::KS];            // A fragments of the current and the next band
+    typedef float accv __attribute__((ext_vector_type(S::ACC)));
+    accv acc[MTW][S::HB][S::NC];       // [band][row block of the band][column block]
+    bf16x8 bfrag[S::KS][S::NC];        // this wave's slice of the resident B tile
+    bf16x8 afrag[2][S::HB][S::KS];     // A fragments of the current and the next band: [band parity][row block][k-slice]
     intx4 a_mant[S::PF][APTN];
     unsigned a_expo[S::PF][APTN];
     intx4 b_raw[BPTN];
@@ -333,7 +363,7 @@ struct TileKernel {
         e_shift = ((((a_q * ACE) % kPanelK) / 8) & 3) * 8;
         // B staging.  The tile is row-major in LDS ([k][n], no padding), cut into slabs of NTS
         // 16-byte slots.  Request i of this wave group fills slab B_FIRST + i: wave w of the group
-        // the 1 KiB at slot 64 w of the slab, lane l the slot l of that.  Chunk c of row k is stored at chunk position c ^ ((k & 3) << SWZ) of its row, so
+        // the 1 KiB at slot 64 w of the slab, lane l the slot l of that.  Chunk c of row k is stored at chunk position c ^ b_swz(k) of its row, so
         // that the rows a transposing read touches fall into different banks.
         const int slot0 = B_FIRST * NTS + __builtin_amdgcn_readfirstlane(wave % (NTS / 64)) * 64;
         const int blk = lane >> 4, j = lane & 15, r = j >> 2;
@@ -347,17 +377,17 @@ struct TileKernel {
             } else {
                 a_wr[b] = a_base + (a_row + A_FIRST * (NTS / A_CPR)) * S::PA + a_q * (ACE * 2);
             }
-            // A fragment: lane l reads row l%32 of a band, k = ks*16 + 8*(l/32) .. +7
-            a_rd[b] = a_base + (wm * 32 + (lane & 31)) * S::PA + (lane >> 5) * 16;
+            // A fragment: lane l reads row l%MB of a row block, k = ks*KM + 8*(l/MB) .. +7
+            a_rd[b] = a_base + (wm * 32 + lane % S::MB) * S::PA + (lane / S::MB) * 16;
         }
         a_w1 = 16;
         if constexpr (S::ASWZ) {
             static_assert(!S::ASWZ || (ACE == 16 && !PAIRK), "swizzled A staging: chunks of two 16-byte pieces, one chunk per row and thread");
             const int wrow = a_row + A_FIRST * (NTS / A_CPR);
             a_w1 = (((wrow >> 1) & 1) != 0) ? -16 : 16;               // piece 2q+1 lands left of piece 2q where the swizzle is odd
-            const int rrow = wm * 32 + (lane & 31), rswz = (rrow >> 1) & 7;
+            const int rrow = wm * 32 + lane % S::MB, rswz = (rrow >> 1) & 7;      // the same for a second row block, 16 rows on
 #pragma unroll
-            for (int ks = 0; ks < S::KS; ++ks) a_rdk[ks] = lds + rrow * S::PA + (((2 * ks + (lane >> 5)) ^ rswz) * 16);
+            for (int ks = 0; ks < S::KS; ++ks) a_rdk[ks] = lds + rrow * S::PA + ((((S::KM / 8) * ks + lane / S::MB) ^ rswz) * 16);
         }
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
@@ -366,20 +396,27 @@ struct TileKernel {
             b_wr[b] = b_req[b] + lane * 16;
             // B fragment through ds_read_b64_tr_b16: within each group of 16 lanes, lane i addresses
             // 4 consecutive columns of row i/4 (8 bytes, half a chunk), and lane j receives column j
-            // of those 4 rows.  The swizzle of row r (mod 4) permutes the chunk index, so each of the
-            // first NBASE column bands gets its own per-lane base; band nt >= 4 adds (nt / 4) * 256 bytes.
+            // of those 4 rows; a second read, 4 rows on, completes the lane's 8 k values.
+            // MB = 32: groups 0, 1 of the wave's four groups of 16 lanes take the two halves of the 32 columns, rows
+            // 0 .. 3 of the k-slice, groups 2, 3 the same columns of rows 8 .. 11.
+            // MB = 16: group g takes the rows 8 g .. 8 g + 3 of the k-slice, all groups the same 16 columns.
+            // The swizzle permutes the chunk index, so each of the first NBASE column blocks gets its own per-lane
+            // base; block nt >= 4 (MB = 32 only) adds (nt / 4) * 256 bytes.
 #pragma unroll
             for (int e = 0; e < NRD; ++e) {
                 if constexpr (BTR) {
-                    // B^T tile [n][k]: lane l reads column (row of B^T) wn*NTW*32 + l%32 and the chunk of k-slice e
-                    // (e = ks: 8 k values from 16 ks + 8 (l/32)); the chunk sits at position chunk ^ ((n / 2) % 8)
+                    // B^T tile [n][k]: lane l reads column (row of B^T) wn*NC*MB + l%MB and the chunk of k-slice e
+                    // (e = ks: 8 k values from KM ks + 8 (l/MB)); the chunk sits at position chunk ^ ((n / 2) % 8)
                     // of its row.  Sixteen lanes (rows n .. n+15) then cover all 64 banks once: row pairs differ in
                     // the position, the two rows of a pair in the half of the banks (pitch 128 bytes).
-                    const int n = wn * S::NTW * 32 + (lane & 31);
-                    b_rd[b][e] = b_base + n * PBT + (((2 * e + (lane >> 5)) ^ ((n >> 1) & 7)) * 16);
+                    const int n = wn * S::NC * S::MB + lane % S::MB;
+                    b_rd[b][e] = b_base + n * PBT + ((((S::KM / 8) * e + lane / S::MB) ^ ((n >> 1) & 7)) * 16);
+                } else if constexpr (S::MB == 32) {
+                    const int chunk = 4 * (wn * S::NC + e) + 2 * (blk & 1) + ((j & 3) >> 1), row = 8 * (blk >> 1) + r;
+                    b_rd[b][e] = b_base + row * S::PB + ((chunk ^ S::b_swz(row)) * 16) + (j & 1) * 8;
                 } else {
-                    const int chunk = 4 * (wn * S::NTW + e) + 2 * (blk & 1) + ((j & 3) >> 1);
-                    b_rd[b][e] = b_base + (8 * (blk >> 1) + r) * S::PB + ((chunk ^ (r << S::SWZ)) * 16) + (j & 1) * 8;
+                    const int chunk = 2 * (wn * S::NC + e) + ((j & 3) >> 1), row = 8 * blk + r;
+                    b_rd[b][e] = b_base + row * S::PB + ((chunk ^ S::b_swz(row)) * 16) + (j & 1) * 8;
                 }
             }
         }
@@ -392,8 +429,8 @@ struct TileKernel {
             for (int b = 0; b < 2; ++b) {
                 char *b_base = lds + S::AB * S::A_BYTES + b * B_BYTES;
                 bt_wr[b] = b_base + b_row * S::PBF + b_q * 32;
-                // B fragment: lane l reads column (row of B^T) l%32 of a band, k = ks*16 + 8*(l/32) .. +7
-                bt_rd[b] = b_base + (wn * S::NTW * 32 + (lane & 31)) * S::PBF + (lane >> 5) * 16;
+                // B fragment: lane l reads column (row of B^T) l%MB of a column block, k = ks*KM + 8*(l/MB) .. +7
+                bt_rd[b] = b_base + (wn * S::NC * S::MB + lane % S::MB) * S::PBF + (lane / S::MB) * 16;
             }
             // rows >= N of B^T lie beyond the end of the planes and read as zero
 #pragma unroll
@@ -432,16 +469,16 @@ struct TileKernel {
                 const int row = slot / (S::T_K / 8), c = (slot % (S::T_K / 8)) ^ ((row >> 1) & 7);
                 b_off[i] = (row * p.K + c * 8) * 2;
             } else {
-                const int row = slot / S::B_CPR, c = (slot % S::B_CPR) ^ ((row & 3) << S::SWZ);
+                const int row = slot / S::B_CPR, c = (slot % S::B_CPR) ^ S::b_swz(row);
                 b_off[i] = (row * p.N + c * 8) * 2;
             }
         }
 #pragma unroll
         for (int a = 0; a < MTW; ++a)
 #pragma unroll
-            for (int b = 0; b < S::NTW; ++b)
+            for (int b = 0; b < S::HB * S::NC; ++b)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+                for (int v = 0; v < S::ACC; ++v) acc[a][b / S::NC][b % S::NC][v] = 0.0f;
         // the offsets above are those of the tile at row 0, column 0; the streams move them to their tiles
         a_m0 = 0;
         b_n0 = 0;
@@ -812,19 +849,19 @@ struct TileKernel {
     }
 
     // ---- LDS -> registers ----------------------------------------------------------------
-    // B fragment (ks, nt) from LDS buffer `buf`: per lane l, column (wn*NTW + nt)*32 + l%32 and
-    // k = ks*16 + 8*(l/32) .. +7.
+    // B fragment (ks, nt) from LDS buffer `buf`: per lane l, column (wn*NC + nt)*MB + l%MB and
+    // k = ks*KM + 8*(l/MB) .. +7.
     template <int ks, int nt>
     ATB_DEV void read_b_frag(int buf)
     {
         if constexpr (BBFP) {
-            bfrag[ks][nt] = *reinterpret_cast<const bf16x8 *>(bt_rd[buf] + nt * 32 * S::PBF + ks * 32);
+            bfrag[ks][nt] = *reinterpret_cast<const bf16x8 *>(bt_rd[buf] + nt * S::MB * S::PBF + ks * S::KM * 2);
         } else if constexpr (BTR) {
             const char *base = (S::NB > 2) ? b_rd[0][ks] + b_read_off : b_rd[buf][ks];
-            bfrag[ks][nt] = *reinterpret_cast<const bf16x8 *>(base + nt * 32 * PBT);
+            bfrag[ks][nt] = *reinterpret_cast<const bf16x8 *>(base + nt * S::MB * PBT);
         } else {
             const char *base = (S::NB > 2) ? b_rd[0][nt % S::NBASE] + b_read_off : b_rd[buf][nt % S::NBASE];
-            const char *src = base + ks * 16 * S::PB + (nt / S::NBASE) * (S::NBASE * 64);
+            const char *src = base + ks * S::KM * S::PB + (nt / S::NBASE) * (S::NBASE * 64);
             typedef __attribute__((address_space(3))) shortx4 lds_shortx4;
             union { shortx4 s[2]; bf16x8 b; } u;
             u.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_shortx4 *)(src));
@@ -836,31 +873,31 @@ struct TileKernel {
     template <int f = 0>
     ATB_DEV void read_b_frags_all(int buf)
     {
-        if constexpr (f < S::KS * S::NTW) {
-            read_b_frag<f / S::NTW, f % S::NTW>(buf);
+        if constexpr (f < S::KS * S::NC) {
+            read_b_frag<f / S::NC, f % S::NC>(buf);
             read_b_frags_all<f + 1>(buf);
         }
     }
 
-    // A fragment (band bd of the sub-tile as band(s, il) gives it, k-slice ks).  In the even deal the bands of the
-    // C tile go round-robin to the wave rows: this wave reads band il*WM + wm of the sub-tile (wm is in a_rd).
-    // The fragments of consecutive bands (counted across sub-tiles) alternate between the two
-    // halves of afrag: `par` is that running band index mod 2.
-    template <int par, int bd, int ks>
+    // A fragment (band bd of the sub-tile as band(s, il) gives it, row block h of the band, k-slice ks).  In the
+    // even deal the bands of the C tile go round-robin to the wave rows: this wave reads band il*WM + wm of the
+    // sub-tile (wm is in a_rd).  The fragments of consecutive bands (counted across sub-tiles) alternate between
+    // the two halves of afrag: `par` is that running band index mod 2.
+    template <int par, int bd, int h, int ks>
     ATB_DEV void read_a_frag(int buf)
     {
         if constexpr (S::ASWZ)       // the k-slice's chunk position depends on the row: one address per k-slice, buffer and band as constants
-            afrag[par][ks] = *reinterpret_cast<const bf16x8 *>(a_rdk[ks] + buf * S::A_BYTES + bd * 32 * S::PA);
+            afrag[par][h][ks] = *reinterpret_cast<const bf16x8 *>(a_rdk[ks] + buf * S::A_BYTES + (bd * 32 + h * S::MB) * S::PA);
         else
-            afrag[par][ks] = *reinterpret_cast<const bf16x8 *>(a_rd[buf] + bd * 32 * S::PA + ks * 32);
+            afrag[par][h][ks] = *reinterpret_cast<const bf16x8 *>(a_rd[buf] + (bd * 32 + h * S::MB) * S::PA + ks * S::KM * 2);
     }
 
-    template <int par, int s, int ks = 0>
+    template <int par, int s, int f = 0>
     ATB_DEV void read_first_band(int buf)
     {
-        if constexpr (ks < S::KS) {
-            read_a_frag<par, band(s, 0), ks>(buf);
-            read_first_band<par, s, ks + 1>(buf);
+        if constexpr (f < S::HB * S::KS) {
+            read_a_frag<par, band(s, 0), f % S::HB, f / S::HB>(buf);
+            read_first_band<par, s, f + 1>(buf);
         }
     }
 
@@ -908,38 +945,63 @@ struct TileKernel {
         }
     }
 
-    // Slot m: one MFMA, then its share of the side work; after the last column band of a k-slice
-    // the A fragment of the same k-slice of the next band; in the last band of the K-step the B
-    // fragment just used is replaced by the next K-step's.  The fences pin this order, so that the
-    // VALU decode and the LDS traffic issue in the shadow of the 8-pass MFMA.
+    // Slot m: MG MFMAs back to back, then the slot's share of the side work; after the last column block of a
+    // (k-slice, row block) the same A fragment of the next band; in the last band of the K-step a B fragment is
+    // replaced by the next K-step's after its last use (second row block).  MFMAs that follow each other share their
+    // A fragment.  The fences pin this order, so that the VALU decode and the LDS traffic issue in the shadow of the MFMAs.
+    static constexpr int MG = ATB_MFMA_GROUP;
+    static_assert(S::NC % MG == 0, "a slot's MFMAs share one A fragment");
+
+    template <int ki, int s, int mm>
+    ATB_DEV void slot_mfma()
+    {
+        constexpr int il = mm / (S::HB * S::KS * S::NC), ks = (mm / (S::HB * S::NC)) % S::KS, h = (mm / S::NC) % S::HB, nt = mm % S::NC;
+        constexpr int local = first_local(s) + il;            // accumulator band of this wave
+        constexpr int par = (bands_before(ki * S::RHO + s) + il) % 2;       // which half of afrag this band uses
+        if constexpr (S::MB == 16)
+            acc[local][h][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfrag[ks][nt], afrag[par][h][ks], acc[local][h][nt], 0, 0, 0);
+        else
+            acc[local][h][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag[ks][nt], afrag[par][h][ks], acc[local][h][nt], 0, 0, 0);
+    }
+
+    template <int ki, int s, int mm>
+    ATB_DEV void slot_reads()
+    {
+        constexpr int il = mm / (S::HB * S::KS * S::NC), ks = (mm / (S::HB * S::NC)) % S::KS, h = (mm / S::NC) % S::HB, nt = mm % S::NC;
+        constexpr int g = ki * S::RHO + s;
+        constexpr int par = (bands_before(g) + il) % 2;
+        if constexpr (nt == S::NC - 1) {
+            if constexpr (il + 1 < per(s))
+                read_a_frag<par ^ 1, band(s, il + 1), h, ks>(g % S::AB);
+            else if constexpr (S::AB == 4)      // first band of the next sub-tile, already complete in LDS
+                read_a_frag<par ^ 1, band((s + 1) % S::RHO, 0), h, ks>((g + 1) % S::AB);
+        }
+        if constexpr (s + 1 == S::RHO && il + 1 == per(s) && h == S::HB - 1) read_b_frag<ks, nt>((ki & 1) ^ 1);
+    }
+
     template <int ki, int s, int m>
     ATB_DEV void slots()
     {
-        if constexpr (m < nm(s)) {
-            constexpr int kpar = ki & 1;
-            constexpr int il = m / (S::KS * S::NTW), ks = (m / S::NTW) % S::KS, nt = m % S::NTW;
-            constexpr int local = first_local(s) + il;            // accumulator band of this wave
-            constexpr bool last_phase = (s + 1 == S::RHO);
+        constexpr int nslot = nm(s) / MG;
+        if constexpr (m < nslot) {
             constexpr int nside = n_side<s>();
-            constexpr int g = ki * S::RHO + s;
-            constexpr int par = (bands_before(g) + il) % 2;       // which half of afrag this band uses
-            if constexpr (COMPUTE)
-                acc[local][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfrag[ks][nt], afrag[par][ks],
-                                                                        acc[local][nt], 0, 0, 0);
+            if constexpr (COMPUTE) {
+                slot_mfma<ki, s, m * MG>();
+                if constexpr (MG >= 2) slot_mfma<ki, s, m * MG + 1>();
+                if constexpr (MG >= 4) { slot_mfma<ki, s, m * MG + 2>(); slot_mfma<ki, s, m * MG + 3>(); }
+            }
             ATB_FENCE();
             // the last eighth of the slots carries no side work, so that the LDS stores of the decode
             // have drained when the wave reaches the switch barrier
-            constexpr int NS = nm(s) - nm(s) / 8;
+            constexpr int NS = nslot - nslot / 8;
             constexpr int j0 = (m * nside) / NS < nside ? (m * nside) / NS : nside;
             constexpr int j1 = ((m + 1) * nside) / NS < nside ? ((m + 1) * nside) / NS : nside;
             side_range<ki, s, j0, j1>();
-            if constexpr (nt == S::NTW - 1 && COMPUTE) {
-                if constexpr (il + 1 < per(s))
-                    read_a_frag<par ^ 1, band(s, il + 1), ks>(g % S::AB);
-                else if constexpr (S::AB == 4)      // first band of the next sub-tile, already complete in LDS
-                    read_a_frag<par ^ 1, band((s + 1) % S::RHO, 0), ks>((g + 1) % S::AB);
+            if constexpr (COMPUTE) {
+                slot_reads<ki, s, m * MG>();
+                if constexpr (MG >= 2) slot_reads<ki, s, m * MG + 1>();
+                if constexpr (MG >= 4) { slot_reads<ki, s, m * MG + 2>(); slot_reads<ki, s, m * MG + 3>(); }
             }
-            if constexpr (last_phase && il + 1 == per(s) && COMPUTE) read_b_frag<ks, nt>(kpar ^ 1);
             ATB_FENCE();
             slots<ki, s, m + 1>();
         }
@@ -1050,9 +1112,9 @@ struct TileKernel {
 #pragma unroll
             for (int a = 0; a < MTW; ++a)
 #pragma unroll
-                for (int b = 0; b < S::NTW; ++b)
+                for (int b = 0; b < S::HB * S::NC; ++b)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.0f;
+                    for (int v = 0; v < S::ACC; ++v) acc[a][b / S::NC][b % S::NC][v] = 0.0f;
         }
         // the requests past the end of the walk (they read zeros) target registers and LDS of this wave
         wait_vm<0>();
@@ -1066,23 +1128,24 @@ struct TileKernel {
         return s * S::SMT + band(s, a - first_local(s));
     }
 
-    // epilogue: fp32 -> bf16 (round to nearest even) and store, once per tile.  Lane l of band
-    // (a, b) holds row l%32 and columns 8*g + 4*(l/32) + 0..3 for g = 0..3.
+    // epilogue: fp32 -> bf16 (round to nearest even) and store, once per tile.  Lane l of block
+    // (a, h, b) holds row l%MB of the block and, in registers 4g .. 4g+3, its columns 8g + 4*(l/MB) + 0..3
+    // (MB = 32: g = 0..3; MB = 16: g = 0 only).
     ATB_DEV void store_c()
     {
         const bool st_vec = (p.N % 4) == 0;
 #pragma unroll
-        for (int a = 0; a < MTW; ++a) {
-            const int m = m0 + (band_of_acc(a) + wm) * 32 + (lane & 31);
+        for (int a = 0; a < S::HB * MTW; ++a) {
+            const int m = m0 + (band_of_acc(a / S::HB) + wm) * 32 + (a % S::HB) * S::MB + lane % S::MB;
 #pragma unroll
-            for (int b = 0; b < S::NTW; ++b) {
-                const int nb = n0 + (wn * S::NTW + b) * 32 + 4 * (lane >> 5);
+            for (int b = 0; b < S::NC; ++b) {
+                const int nb = n0 + (wn * S::NC + b) * S::MB + 4 * (lane / S::MB);
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
+                for (int g = 0; g < S::ACC / 4; ++g) {
                     const int n = nb + 8 * g;
                     bf16x4 o;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[a][b][4 * g + e];
+                    for (int e = 0; e < 4; ++e) o[e] = (__bf16)acc[a / S::HB][a % S::HB][b][4 * g + e];
                     if (m < p.M && n < p.N) {
                         uint16_t *dst = p.C + (int64_t)m * p.N + n;
                         if (st_vec && n + 4 <= p.N) {
@@ -1101,29 +1164,29 @@ struct TileKernel {
     }
 
     // Epilogue for C in BFP16 (blocks of 8 along N): a block is the 4 consecutive columns of lane l
-    // plus the 4 of lane l ^ 32 (same row).  Same arithmetic as the stand-alone quantiser: shared
+    // plus the 4 of lane l ^ MB (same row).  Same arithmetic as the stand-alone quantiser: shared
     // exponent = largest fp32 exponent field, mantissa = clamp(rne(x * 2^(133 - E)), +-127).
     // Needs N % 8 == 0; columns N .. 64 * n_panels - 1 (the tail of C's last panel) are written as zero.
     ATB_DEV void store_c_bfp()
     {
 #pragma unroll
-        for (int a = 0; a < MTW; ++a) {
-            const int m = m0 + (band_of_acc(a) + wm) * 32 + (lane & 31);
+        for (int a = 0; a < S::HB * MTW; ++a) {
+            const int m = m0 + (band_of_acc(a / S::HB) + wm) * 32 + (a % S::HB) * S::MB + lane % S::MB;
 #pragma unroll
-            for (int b = 0; b < S::NTW; ++b) {
-                const int nb = n0 + (wn * S::NTW + b) * 32 + 4 * (lane >> 5);
+            for (int b = 0; b < S::NC; ++b) {
+                const int nb = n0 + (wn * S::NC + b) * S::MB + 4 * (lane / S::MB);
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
+                for (int g = 0; g < S::ACC / 4; ++g) {
                     const int n = nb + 8 * g;
                     const bool live = (n < p.N);           // whole blocks: N % 8 == 0
                     float x[4];
                     unsigned e = 0;
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
-                        x[t] = live ? acc[a][b][4 * g + t] : 0.0f;
+                        x[t] = live ? acc[a / S::HB][a % S::HB][b][4 * g + t] : 0.0f;
                         e = max(e, (__float_as_uint(x[t]) >> 23) & 0xFFu);
                     }
-                    const unsigned other = (unsigned)__builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, (int)e);
+                    const unsigned other = (unsigned)__builtin_amdgcn_ds_bpermute((lane ^ S::MB) << 2, (int)e);
                     e = max(e, other);
                     const int sh = 133 - (int)e;
                     unsigned w = 0;
@@ -1136,7 +1199,7 @@ struct TileKernel {
                     if (m < p.M && n < p.n_panels * kPanelK) {
                         const int64_t rec = (int64_t)(n / kPanelK) * p.M + m;       // (panel, row)
                         *reinterpret_cast<unsigned *>(p.Cm + rec * kPanelK + n % kPanelK) = w;
-                        if ((lane >> 5) == 0) p.Ce[rec * (kPanelK / 8) + ((n % kPanelK) >> 3)] = (uint8_t)e;
+                        if (((lane / S::MB) & 1) == 0) p.Ce[rec * (kPanelK / 8) + ((n % kPanelK) >> 3)] = (uint8_t)e;
                     }
                 }
             }
@@ -1364,8 +1427,9 @@ const Instance g_instances[] = {
     make_instance<Shape<64, 64, 128, 128, 2, 2, 2, 2, -1, 0, 2, 2, 4>, true>(0.83, 1.0),
     // Small tiles for small problems: four and six workgroups per CU, with 4 and 2 helper waves (workgroups that
     // share a CU hide each other's barriers and latencies better than the issue model allows for: measured factors).
-    make_instance<Shape<64, 64, 64, 64, 2, 2, 2, 2, -1, 0, 2, 2, 4>, true>(1.2),
-    make_instance<Shape<32, 64, 64, 64, 1, 2, 2, 2, -1, 0, 2, 2, 2>, true>(1.24),
+    // (several of these small workgroups share a CU, so a SIMD has several multiplying waves: MB = 16, +3-5 %)
+    make_instance<Shape<64, 64, 64, 64, 2, 2, 2, 2, -1, 0, 2, 2, 4, false, 0, 16>, true>(1.2),
+    make_instance<Shape<32, 64, 64, 64, 1, 2, 2, 2, -1, 0, 2, 2, 2, false, 0, 16>, true>(1.24),
     // Skinny problems (M <= 128 or so at large N, K: one or two rows of C tiles, fewer workgroups than CUs) are
     // bound by what each workgroup keeps in flight and by how fast its few waves get through a K-step, not by
     // bandwidth.  These two instances have K-steps of 256 (four times the bytes per round trip), a ring of three
