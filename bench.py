@@ -362,20 +362,21 @@ def main():
         sink = torch.empty(256 * 512, dtype=torch.float32, device="cuda")
         clk = torch.zeros(2, dtype=torch.int64, device="cuda")
         probe = {}
-        for name, rnd in (("random_bf16", True), ("constant", False)):
+        # the 16 x 16 x 32 form is the one the large tiles use (and the cheaper one in power); 32 x 32 x 16 for comparison
+        for name, rnd, rows in (("random_bf16", True, 16), ("constant", False, 16), ("random_bf16_32x32x16", True, 32)):
             iters = 800
             for _ in range(60):
-                atb.mfma_probe(sink, clk, 256, iters, rnd)
+                atb.mfma_probe(sink, clk, 256, iters, rnd, mfma_rows=rows)
             torch.cuda.synchronize()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             e0.record()
             for _ in range(20):
-                pflop = atb.mfma_probe(sink, clk, 256, iters, rnd)
+                pflop = atb.mfma_probe(sink, clk, 256, iters, rnd, mfma_rows=rows)
             e1.record()
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1) / 20
             ticks = clk.cpu().numpy()
-            probe[name] = {"tflops": round(pflop / (ms * 1e-3) / 1e12, 1), "kernel_ms": round(ms, 4),
+            probe[name] = {"mfma": "16x16x32" if rows == 16 else "32x32x16", "tflops": round(pflop / (ms * 1e-3) / 1e12, 1), "kernel_ms": round(ms, 4),
                            "clock_mhz_from_mfma_rate": round(2 * iters * 32 * 32 / (ms * 1e-3) / 1e6, 0),
                            "s_memtime_ticks": int(ticks[0]), "s_memrealtime_ticks": int(ticks[1])}
         pclock = clock_under(lambda: atb.mfma_probe(sink, clk, 256, 800, True), 300)

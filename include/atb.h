@@ -250,14 +250,18 @@ atb_status atb_select_tiles(int64_t M, int64_t N, int64_t K, const atb_hw_params
  *   switch = (120 + 4.7 * first-band reads + 150) / waves per SIMD
  *                                               prolog (LDS latency, Eq. 4 form) + epilog (barrier)
  *   kstep  = steady + rho * switch              (Eq. 9; workgroups sharing a CU overlap, Eq. 10)
+ * (n_mfma counts units of 32 x 32 x 16 = 32768 flop: one v_mfma_f32_32x32x16_bf16 or two
+ * v_mfma_f32_16x16x32_bf16, which cost the same pipe and port cycles.)
  * mfma_util = mfma / kstep; the chip is power-limited under this kernel, the
- * measured clock follows 1.339 GHz * mfma_util^-0.617 (capped at 2.4), and
+ * measured clock follows c * mfma_util^-0.617 (capped at 2.4 GHz) with c = 1.339 GHz for
+ * instances that multiply with the 32 x 32 x 16 form and 1.457 GHz for the 16 x 16 x 32
+ * form, which draws less power per flop, and
  * pred_flops = flop per K-step * CUs / (kstep / clock).
  * Predicts the full-load throughput of the compiled instances within 15 %
  * from the tile factors and the wave grid alone (measured values: tests/measured/mi355x_instances.txt);
  * it does not see pipeline stalls of a particular schedule. */
 typedef struct atb_micro_model {
-    double n_mfma;         /* MFMAs per C tile and K-step */
+    double n_mfma;         /* MFMA units (32768 flop) per C tile and K-step */
     double mfma_cycles, valu_cycles, lds_cycles, vmem_cycles;
     double steady_cycles;  /* II of one K-step */
     double switch_cycles;  /* prolog + epilog of one microkernel call */
@@ -268,14 +272,15 @@ typedef struct atb_micro_model {
 } atb_micro_model;
 
 /* wave_m x wave_n: the wave grid of the workgroup (64-lane waves); wg_per_cu:
- * workgroups that share a CU.  ATB_ERR_INVALID_ARG / ATB_ERR_BAD_TILE if the
- * factors do not divide (32-row bands per wave row, 32-column bands per wave
- * column, T_K % 16). */
+ * workgroups that share a CU; mfma_rows: 16 or 32, the form of the MFMA.
+ * ATB_ERR_INVALID_ARG / ATB_ERR_BAD_TILE if the factors do not divide (32-row
+ * bands per wave row, 32-column bands per wave column, T_K % 16). */
 atb_status atb_model_microkernel(int T_MA, int T_MC, int T_K, int T_N, int wave_m, int wave_n,
-                                 int wg_per_cu, atb_micro_model *out);
+                                 int wg_per_cu, int mfma_rows, atb_micro_model *out);
 
-/* Wave grid and residency of compiled instance `index` (inputs of the call above). */
-atb_status atb_instance_geometry(int index, int *wave_m, int *wave_n, int *wg_per_cu);
+/* Wave grid, residency and MFMA form of compiled instance `index` (inputs of the call above;
+ * any of the four pointers may be NULL). */
+atb_status atb_instance_geometry(int index, int *wave_m, int *wave_n, int *wg_per_cu, int *mfma_rows);
 
 /* ------------------------------------------------------- measurement aid */
 
@@ -285,7 +290,10 @@ atb_status atb_instance_geometry(int index, int *wave_m, int *wave_n, int *wg_pe
  * assumes a clock the chip does not hold under full matrix load).  Not a step
  * of the GEMM.
  * Launches `workgroups` workgroups of 8 waves (two per SIMD, as the GEMM's
- * large tiles); each wave issues iters * 32 v_mfma_f32_32x32x16_bf16 on
+ * large tiles); each wave issues iters * 32 v_mfma_f32_32x32x16_bf16
+ * (mfma_rows = 32) or iters * 64 v_mfma_f32_16x16x32_bf16 (mfma_rows = 16:
+ * the same flop; the form the large GEMM tiles use, and the one that draws
+ * less power) on
  * operands that rotate over four register sets; random_operands != 0 fills
  * them with pseudo-random bf16 (random sign and mantissa, exponents 2^-7 .. 2),
  * 0 with the constant 1.0 (which draws less power, hence a higher clock).
@@ -295,9 +303,10 @@ atb_status atb_instance_geometry(int index, int *wave_m, int *wave_n, int *wg_pe
  * (s_memtime; measured on MI355X: one tick per two shader cycles) and of the
  * constant-rate counter (s_memrealtime).
  * *flop (HOST, may be NULL) receives the floating-point operations of the
- * launch.  Async on hip_stream; workgroups in [1, 65536], iters in [1, 2^20]. */
+ * launch.  Async on hip_stream; workgroups in [1, 65536], iters in [1, 2^20],
+ * mfma_rows 16 or 32 (anything else: ATB_ERR_INVALID_ARG). */
 atb_status atb_mfma_probe(void *sink_dev, void *clocks_dev, int workgroups, int iters,
-                          int random_operands, void *hip_stream, double *flop);
+                          int random_operands, int mfma_rows, void *hip_stream, double *flop);
 
 #ifdef __cplusplus
 }

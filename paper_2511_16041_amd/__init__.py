@@ -112,11 +112,11 @@ def lib() -> ctypes.CDLL:
     L.atb_select_tiles.restype = ci
     L.atb_select_tiles.argtypes = [i64, i64, i64, ctypes.POINTER(HwParams), ctypes.POINTER(Choice), ci, pi]
     L.atb_model_microkernel.restype = ci
-    L.atb_model_microkernel.argtypes = [ci, ci, ci, ci, ci, ci, ci, ctypes.POINTER(MicroModel)]
+    L.atb_model_microkernel.argtypes = [ci, ci, ci, ci, ci, ci, ci, ci, ctypes.POINTER(MicroModel)]
     L.atb_instance_geometry.restype = ci
-    L.atb_instance_geometry.argtypes = [ci, pi, pi, pi]
+    L.atb_instance_geometry.argtypes = [ci, pi, pi, pi, pi]
     L.atb_mfma_probe.restype = ci
-    L.atb_mfma_probe.argtypes = [vp, vp, ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
+    L.atb_mfma_probe.argtypes = [vp, vp, ci, ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
     _lib = L
     return L
 
@@ -197,15 +197,17 @@ def model_eval(M: int, N: int, K: int, T_MA: int, T_MC: int, T_K: int, T_N: int,
     return ch
 
 
-def instance_geometry(index: int) -> Tuple[int, int, int]:
-    a, b, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
-    _check(lib().atb_instance_geometry(index, a, b, c), "atb_instance_geometry")
-    return a.value, b.value, c.value
+def instance_geometry(index: int) -> Tuple[int, int, int, int]:
+    """(wave_m, wave_n, workgroups per CU, rows of the MFMA form: 16 or 32) of compiled instance `index`."""
+    a, b, c, d = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    _check(lib().atb_instance_geometry(index, a, b, c, d), "atb_instance_geometry")
+    return a.value, b.value, c.value, d.value
 
 
-def model_microkernel(T_MA: int, T_MC: int, T_K: int, T_N: int, wave_m: int, wave_n: int, wg_per_cu: int) -> MicroModel:
+def model_microkernel(T_MA: int, T_MC: int, T_K: int, T_N: int, wave_m: int, wave_n: int, wg_per_cu: int,
+                      mfma_rows: int) -> MicroModel:
     m = MicroModel()
-    _check(lib().atb_model_microkernel(T_MA, T_MC, T_K, T_N, wave_m, wave_n, wg_per_cu, ctypes.byref(m)),
+    _check(lib().atb_model_microkernel(T_MA, T_MC, T_K, T_N, wave_m, wave_n, wg_per_cu, mfma_rows, ctypes.byref(m)),
            "atb_model_microkernel")
     return m
 
@@ -247,15 +249,16 @@ def bfp16_decode(A_bfp, M: int, K: int, stream=None):
     return out
 
 
-def mfma_probe(sink, clocks, workgroups: int, iters: int, random_operands: bool = True, stream=None) -> float:
+def mfma_probe(sink, clocks, workgroups: int, iters: int, random_operands: bool = True, stream=None, mfma_rows: int = 16) -> float:
     """Launch the MFMA-only measurement loop (atb_mfma_probe).  sink: CUDA float32 tensor of at least
-    workgroups * 512 elements; clocks: CUDA int64 tensor of 2 elements, or None.  Returns the launch's flop."""
+    workgroups * 512 elements; clocks: CUDA int64 tensor of 2 elements, or None; mfma_rows: 16 (16 x 16 x 32 MFMAs, the
+    form of the large GEMM tiles) or 32 (32 x 32 x 16).  Returns the launch's flop."""
     import torch
     assert sink.is_cuda and sink.dtype == torch.float32 and sink.numel() >= workgroups * 512
     assert clocks is None or (clocks.is_cuda and clocks.dtype == torch.int64 and clocks.numel() >= 2)
     flop = ctypes.c_double()
     _check(lib().atb_mfma_probe(ctypes.c_void_p(sink.data_ptr()), ctypes.c_void_p(clocks.data_ptr()) if clocks is not None else None,
-                                workgroups, iters, 1 if random_operands else 0, _stream_ptr(stream), ctypes.byref(flop)),
+                                workgroups, iters, 1 if random_operands else 0, mfma_rows, _stream_ptr(stream), ctypes.byref(flop)),
            "atb_mfma_probe")
     return flop.value
 

@@ -216,11 +216,12 @@ extern "C" atb_status atb_gemm_launch_info(const atb_gemm *g, int64_t *workgroup
 }
 
 extern "C" atb_status atb_mfma_probe(void *sink, void *clocks, int workgroups, int iters, int random_operands,
-                                     void *stream, double *flop)
+                                     int mfma_rows, void *stream, double *flop)
 {
     if (!sink || workgroups < 1 || workgroups > 65536 || iters < 1 || iters > (1 << 20)) return ATB_ERR_INVALID_ARG;
+    if (mfma_rows != 16 && mfma_rows != 32) return ATB_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(sink) & 3u) != 0 || (reinterpret_cast<uintptr_t>(clocks) & 7u) != 0) return ATB_ERR_INVALID_ARG;
     if (flop) *flop = atb::mfma_probe_flop(workgroups, iters);
     return hip_status(atb::launch_mfma_probe(static_cast<float *>(sink), static_cast<unsigned long long *>(clocks), workgroups,
-                                             iters, random_operands != 0, static_cast<hipStream_t>(stream)));
+                                             iters, random_operands != 0, mfma_rows, static_cast<hipStream_t>(stream)));
 }

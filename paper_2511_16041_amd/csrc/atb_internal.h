@@ -33,6 +33,7 @@ struct Instance {
     int threads;            // wave_m * wave_n * 64
     int lds_bytes;          // static LDS of the kernel
     int wg_per_cu;          // workgroups of this instance that share a CU
+    int mfma_rows;          // 16: v_mfma_f32_16x16x32_bf16, 32: v_mfma_f32_32x32x16_bf16
     double eff_scale;       // measured full-load throughput of this instance relative to Eq. (12)'s fit; 0: taken from the issue model
     double lone_cap;        // measured largest gain of a workgroup in a sparsely filled round; 0: the default for wg_per_cu
     hipError_t (*launch)(const GemmParams &p, hipStream_t stream);
@@ -51,7 +52,7 @@ hipError_t launch_quantize(const float *A, int64_t lda, int8_t *Am, uint8_t *Ae,
 hipError_t launch_decode(const int8_t *Am, const uint8_t *Ae, uint16_t *out, int64_t M, int64_t K,
                          hipStream_t stream);
 // MFMA-only measurement loop (atb_probe.hip)
-hipError_t launch_mfma_probe(float *sink, unsigned long long *clocks, int workgroups, int iters, int random, hipStream_t stream);
+hipError_t launch_mfma_probe(float *sink, unsigned long long *clocks, int workgroups, int iters, int random, int mfma_rows, hipStream_t stream);
 double mfma_probe_flop(int workgroups, int iters);
 size_t mfma_probe_sink_bytes(int workgroups);
 constexpr int kPanelK = 64;      // K extent of a panel of the BFP16 layout

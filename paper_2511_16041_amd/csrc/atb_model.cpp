@@ -93,14 +93,14 @@ extern "C" void atb_hw_params_mi355x(atb_hw_params *hw)
     hw->buffer_bytes = 160.0 * 1024.0;           // LDS per CU
     hw->acc_bytes = 256.0 * 1024.0;              // 4 waves x 256 accumulator VGPRs x 64 lanes x 4 B
     // Least-squares fit to the measured K-step times of the 256x256x64 instances at rho = 1, 2, 4, 8
-    // on 8192^3 (in cycles of the nominal 2.4 GHz clock): 3792 + 138 rho + 197 / rho, against 2048
-    // cycles of MFMA issue, i.e. Eff_micro(64) = 0.540.  T_K = 128 measured no better than 64, so the
+    // on 8192^3 (in cycles of the nominal 2.4 GHz clock): 3744 + 140 rho + 68 / rho, against 2048
+    // cycles of MFMA issue, i.e. Eff_micro(64) = 0.547.  T_K = 128 measured no better than 64, so the
     // fit saturates early (small eps): Eff_micro ~ 1 / II.
-    hw->delta_cycles = 138.0;
-    hw->fill_cycles = 197.0;
+    hw->delta_cycles = 140.0;
+    hw->fill_cycles = 68.0;
     hw->eta = 1.0;
     hw->eps = 0.4;
-    hw->II = 1.8453;
+    hw->II = 1.8221;
     hw->a_bytes = 1.125;                         // A BFP16: 9 bytes per 8 elements
     hw->b_bytes = 2.0;
     hw->c_bytes = 2.0;
@@ -164,11 +164,11 @@ extern "C" atb_status atb_model_eval(int64_t M, int64_t N, int64_t K, int T_MA, 
 // normalised by the same ratio for the symmetric 256 x 256 x 64 x 256 instance (where the fit was made).
 double instance_factor(const atb::Instance &x)
 {
-    auto ratio = [](int T_MA, int T_MC, int T_K, int T_N, int wm, int wn, int wg) {
+    auto ratio = [](int T_MA, int T_MC, int T_K, int T_N, int wm, int wn, int wg, int rows) {
         atb_micro_model mm;
         atb_choice ch;
         // a problem large enough that neither round quantisation nor the launch cost matters
-        if (atb_model_microkernel(T_MA, T_MC, T_K, T_N, wm, wn, wg, &mm) != ATB_OK ||
+        if (atb_model_microkernel(T_MA, T_MC, T_K, T_N, wm, wn, wg, rows, &mm) != ATB_OK ||
             atb_model_eval((int64_t)1 << 20, (int64_t)1 << 20, (int64_t)1 << 16, T_MA, T_MC, T_K, T_N, nullptr, &ch) != ATB_OK ||
             ch.eff_core <= 0.0)
             return 0.0;
@@ -176,8 +176,8 @@ double instance_factor(const atb::Instance &x)
         atb_hw_params_mi355x(&hw);
         return mm.pred_flops / (ch.eff_core * hw.peak_core_flops * hw.n_core);
     };
-    const double ref = ratio(256, 256, 64, 256, 2, 4, 1);
-    const double own = ratio(x.T_MA, x.T_MC, x.T_K, x.T_N, x.wave_m, x.wave_n, x.wg_per_cu);
+    const double ref = ratio(256, 256, 64, 256, 2, 4, 1, 16);
+    const double own = ratio(x.T_MA, x.T_MC, x.T_K, x.T_N, x.wave_m, x.wave_n, x.wg_per_cu, x.mfma_rows);
     return (ref > 0.0 && own > 0.0) ? own / ref : 1.0;
 }
 
@@ -230,9 +230,10 @@ extern "C" atb_status atb_select_tiles(int64_t M, int64_t N, int64_t K, const at
 }
 
 extern "C" atb_status atb_model_microkernel(int T_MA, int T_MC, int T_K, int T_N, int wave_m, int wave_n,
-                                            int wg_per_cu, atb_micro_model *out)
+                                            int wg_per_cu, int mfma_rows, atb_micro_model *out)
 {
-    if (!out || T_MA < 1 || T_MC < 1 || T_K < 1 || T_N < 1 || wave_m < 1 || wave_n < 1 || wg_per_cu < 1)
+    if (!out || T_MA < 1 || T_MC < 1 || T_K < 1 || T_N < 1 || wave_m < 1 || wave_n < 1 || wg_per_cu < 1 ||
+        (mfma_rows != 16 && mfma_rows != 32))
         return ATB_ERR_INVALID_ARG;
     if (T_MC % T_MA != 0 || T_K % 16 != 0 || T_MC % (32 * wave_m) != 0 || T_N % (32 * wave_n) != 0) return ATB_ERR_BAD_TILE;
     // unit costs, shader-clock cycles (measured, see the header)
@@ -258,18 +259,20 @@ extern "C" atb_status atb_model_microkernel(int T_MA, int T_MC, int T_K, int T_N
     m.switch_cycles = (kLdsLatency + waves * ks * kReadB128 + kBarrier) / std::max(1.0, waves_per_simd);
     m.kstep_cycles = m.steady_cycles + rho * m.switch_cycles;
     m.mfma_util = m.mfma_cycles / m.kstep_cycles;
-    m.clock_hz = std::min(2.4e9, 1.339e9 * std::pow(m.mfma_util, -0.617));
+    // the 16 x 16 x 32 form of the MFMA draws less power per flop, which the chip turns into clock
+    m.clock_hz = std::min(2.4e9, (mfma_rows == 16 ? 1.457e9 : 1.339e9) * std::pow(m.mfma_util, -0.617));
     m.pred_flops = m.n_mfma * 32768.0 * 256.0 / (m.kstep_cycles / m.clock_hz);
     *out = m;
     return ATB_OK;
 }
 
-extern "C" atb_status atb_instance_geometry(int index, int *wave_m, int *wave_n, int *wg_per_cu)
+extern "C" atb_status atb_instance_geometry(int index, int *wave_m, int *wave_n, int *wg_per_cu, int *mfma_rows)
 {
     if (index < 0 || index >= atb::instance_count()) return ATB_ERR_INVALID_ARG;
     const atb::Instance &x = atb::instance(index);
     if (wave_m) *wave_m = x.wave_m;
     if (wave_n) *wave_n = x.wave_n;
     if (wg_per_cu) *wg_per_cu = x.wg_per_cu;
+    if (mfma_rows) *mfma_rows = x.mfma_rows;
     return ATB_OK;
 }

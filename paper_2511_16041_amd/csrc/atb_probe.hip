@@ -10,9 +10,10 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kProbeThreads = 512;          // 8 waves, two per SIMD, as the GEMM's large tiles
-constexpr int kProbeMfmaPerIter = 32;       // per wave: what one K-step of a 256 x 256 x 64 tile gives a wave
+constexpr int kProbeMfmaPerIter = 32;       // per wave, in units of 32768 flop (one 32 x 32 x 16 MFMA or two 16 x 16 x 32): what one K-step of a 256 x 256 x 64 tile gives a wave
 
 // two bf16 with random sign and mantissa and exponents 2^-7 .. 2 (or the constant 1.0 when `random` is 0)
 __device__ __forceinline__ unsigned probe_operand(unsigned &r, int random)
@@ -21,6 +22,8 @@ __device__ __forceinline__ unsigned probe_operand(unsigned &r, int random)
     return random ? ((r & 0x807F807Fu) | 0x3C003C00u | ((r >> 3) & 0x03800380u)) : 0x3F803F80u;
 }
 
+// MB = 32: v_mfma_f32_32x32x16_bf16, MB = 16: v_mfma_f32_16x16x32_bf16 (twice as many instructions for the same flop)
+template <int MB>
 __global__ void __launch_bounds__(kProbeThreads) mfma_probe_kernel(float *sink, unsigned long long *clocks, int iters, int random)
 {
     unsigned r = threadIdx.x * 2654435761u + 12345u + blockIdx.x;
@@ -33,25 +36,30 @@ __global__ void __launch_bounds__(kProbeThreads) mfma_probe_kernel(float *sink, 
         a[s] = ua.v;
         b[s] = ub.v;
     }
-    floatx16 acc[8];
+    constexpr int NACC = (MB == 32) ? 8 : 16, NV = MB * MB / 64, NMFMA = kProbeMfmaPerIter * (32 / MB);
+    typedef float accv __attribute__((ext_vector_type(NV)));
+    accv acc[NACC];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < NACC; ++i)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
+        for (int v = 0; v < NV; ++v) acc[i][v] = 0.0f;
     const unsigned long long c0 = __builtin_amdgcn_s_memtime(), w0 = __builtin_amdgcn_s_memrealtime();
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int i = 0; i < kProbeMfmaPerIter; ++i) {
+        for (int i = 0; i < NMFMA; ++i) {
             // the operands rotate over four register sets each, so they change from one MFMA to the next
-            acc[i % 8] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i % 4], b[(i / 4) % 4], acc[i % 8], 0, 0, 0);
+            if constexpr (MB == 32)
+                acc[i % NACC] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i % 4], b[(i / 4) % 4], acc[i % NACC], 0, 0, 0);
+            else
+                acc[i % NACC] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i % 4], b[(i / 4) % 4], acc[i % NACC], 0, 0, 0);
         }
     }
     const unsigned long long c1 = __builtin_amdgcn_s_memtime(), w1 = __builtin_amdgcn_s_memrealtime();
     float s = 0.0f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < NACC; ++i)
 #pragma unroll
-        for (int q = 0; q < 16; ++q) s += acc[i][q];
+        for (int q = 0; q < NV; ++q) s += acc[i][q];
     sink[(size_t)blockIdx.x * kProbeThreads + threadIdx.x] = s;
     if (clocks && blockIdx.x == 0 && threadIdx.x == 0) {
         clocks[0] = c1 - c0;      // s_memtime ticks
@@ -61,9 +69,12 @@ __global__ void __launch_bounds__(kProbeThreads) mfma_probe_kernel(float *sink, 
 
 }  // namespace
 
-hipError_t launch_mfma_probe(float *sink, unsigned long long *clocks, int workgroups, int iters, int random, hipStream_t stream)
+hipError_t launch_mfma_probe(float *sink, unsigned long long *clocks, int workgroups, int iters, int random, int mfma_rows, hipStream_t stream)
 {
-    hipLaunchKernelGGL(mfma_probe_kernel, dim3(workgroups), dim3(kProbeThreads), 0, stream, sink, clocks, iters, random);
+    if (mfma_rows == 32)
+        hipLaunchKernelGGL(mfma_probe_kernel<32>, dim3(workgroups), dim3(kProbeThreads), 0, stream, sink, clocks, iters, random);
+    else
+        hipLaunchKernelGGL(mfma_probe_kernel<16>, dim3(workgroups), dim3(kProbeThreads), 0, stream, sink, clocks, iters, random);
     return hipGetLastError();
 }
 

@@ -16,6 +16,7 @@
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef int intx4 __attribute__((ext_vector_type(4)));
 typedef short shortx4 __attribute__((ext_vector_type(4)));
 
@@ -111,6 +112,68 @@ double run(float *out, int iters)     // nanoseconds per iteration
     CK(hipEventElapsedTime(&ms, e0, e1));
     return ms * 1e6 / iters;
 }
+
+// The 16 x 16 x 32 form of the bf16 MFMA (half the flop per instruction, the same peak rate): RND 0 constant, 1
+// pseudo-random operands; HALFPAIRS BFP16 decode pairs per TWO MFMAs (i.e. per 32768 flop, the unit of cost_kernel),
+// issued after the second MFMA of each pair.
+template <int RND, int HALFPAIRS>
+__global__ void __launch_bounds__(kThreads) cost16_kernel(float *out, int iters, int seed)
+{
+    const int t = threadIdx.x;
+    bf16x8 a, b;
+    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)(float)((t + e) % 3); b[e] = (__bf16)(float)((t + e) % 5); }
+    if (RND) {
+        union { unsigned u[4]; bf16x8 v; } ua, ub;
+        unsigned r = t * 2654435761u + 12345u;
+        for (int e = 0; e < 4; ++e) {
+            r = r * 1664525u + 1013904223u; ua.u[e] = (r & 0x807F807Fu) | 0x3C003C00u | ((r >> 3) & 0x03800380u);
+            r = r * 1664525u + 1013904223u; ub.u[e] = (r & 0x807F807Fu) | 0x3C003C00u | ((r >> 3) & 0x03800380u);
+        }
+        a = ua.v; b = ub.v;
+    }
+    floatx4 acc[16];
+    for (int i = 0; i < 16; ++i) for (int v = 0; v < 4; ++v) acc[i][v] = 0.f;
+    int w0 = seed + t, sh = seed & 3;
+    unsigned dsum = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[i], 0, 0, 0);
+            FENCE();
+            if (i & 1) {
+#pragma unroll
+                for (int v = 0; v < HALFPAIRS; ++v) {
+                    const float f0 = ldexpf(byte_to_float(w0, (2 * v) & 3), sh), f1 = ldexpf(byte_to_float(w0, (2 * v + 1) & 3), sh);
+                    union { bf16x2 p; unsigned u; } pk;
+                    pk.p = bf16x2{(__bf16)f0, (__bf16)f1};
+                    dsum ^= pk.u;
+                    w0 += 0x01010101;
+                }
+            }
+            FENCE();
+        }
+    }
+    float s = (float)dsum;
+    for (int i = 0; i < 16; ++i) for (int q = 0; q < 4; ++q) s += acc[i][q];
+    out[blockIdx.x * kThreads + t] = s;
+}
+
+template <int RND, int HALFPAIRS>
+double run16(float *out, int iters)     // nanoseconds per iteration
+{
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0)); CK(hipEventCreate(&e1));
+    hipLaunchKernelGGL((cost16_kernel<RND, HALFPAIRS>), dim3(kBlocks), dim3(kThreads), 0, 0, out, 200, 1);
+    CK(hipDeviceSynchronize());
+    CK(hipEventRecord(e0));
+    hipLaunchKernelGGL((cost16_kernel<RND, HALFPAIRS>), dim3(kBlocks), dim3(kThreads), 0, 0, out, iters, 1);
+    CK(hipEventRecord(e1));
+    CK(hipEventSynchronize(e1));
+    float ms;
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    return ms * 1e6 / iters;
+}
+
 
 __device__ __forceinline__ unsigned rnd_bf16x2(unsigned &r) { r = r * 1664525u + 1013904223u; return (r & 0x807F807Fu) | 0x3C003C00u | ((r >> 3) & 0x03800380u); }
 
@@ -301,5 +364,15 @@ int main()
     op_cost<7>(out, "v_perm_b32");
     op_cost<8>(out, "v_pk_add_u16");
     op_cost<9>(out, "v_bfe_u32");
+    // the 16 x 16 x 32 form: an iteration issues 16 MFMAs per wave = 32 per SIMD = 16 units of 32768 flop per SIMD
+    double d[4];
+    d[0] = run16<0, 0>(out, iters) / 16.0; printf("cost16_kernel<0,0> MFMA 16x16x32 bf16, 0 decode pairs per 2 MFMAs: %6.2f ns per 2 MFMAs per SIMD\n", d[0]);
+    d[1] = run16<0, 1>(out, iters) / 16.0; printf("cost16_kernel<0,1> MFMA 16x16x32 bf16, 1 decode pair  per 2 MFMAs: %6.2f ns per 2 MFMAs per SIMD\n", d[1]);
+    d[2] = run16<0, 2>(out, iters) / 16.0; printf("cost16_kernel<0,2> MFMA 16x16x32 bf16, 2 decode pairs per 2 MFMAs: %6.2f ns per 2 MFMAs per SIMD\n", d[2]);
+    d[3] = run16<0, 3>(out, iters) / 16.0; printf("cost16_kernel<0,3> MFMA 16x16x32 bf16, 3 decode pairs per 2 MFMAs: %6.2f ns per 2 MFMAs per SIMD\n", d[3]);
+    x = run16<0, 0>(out, 1000000) / 16.0; printf("cost16_kernel<0,0> MFMA only, constant operands, 1e6 iterations: %6.2f ns per 2 MFMAs per SIMD = %.0f TFLOP/s\n", x, 32768.0 * 1024 / x / 1e3);
+    x = run16<1, 0>(out, 1000000) / 16.0; printf("cost16_kernel<1,0> MFMA only, random operands,   1e6 iterations: %6.2f ns per 2 MFMAs per SIMD = %.0f TFLOP/s\n", x, 32768.0 * 1024 / x / 1e3);
+    x = run16<1, 1>(out, 1000000) / 16.0; printf("cost16_kernel<1,1> random operands + 1 decode pair per 2 MFMAs:  %6.2f ns per 2 MFMAs per SIMD = %.0f TFLOP/s\n", x, 32768.0 * 1024 / x / 1e3);
+    x = run<4, 0>(out, 1000000) / 16.0; printf("cost_kernel<4,0>  32x32x16 again, random operands, 1e6 iterations: %6.2f ns per MFMA per SIMD = %.0f TFLOP/s\n", x, 32768.0 * 1024 / x / 1e3);
     return 0;
 }

@@ -96,8 +96,10 @@ static void api_paths()
     EXPECT(atb_instance_get(1, nullptr, nullptr, nullptr, nullptr) == ATB_OK);
     EXPECT(atb_instance_get(-1, &a, &b, &c, &d) == ATB_ERR_INVALID_ARG);
     EXPECT(atb_instance_get(4, &a, &b, &c, &d) == ATB_ERR_INVALID_ARG);
-    EXPECT(atb_instance_geometry(3, &a, &b, &c) == ATB_OK && a == 1 && b == 2 && c == 6);
-    EXPECT(atb_instance_geometry(9, &a, &b, &c) == ATB_ERR_INVALID_ARG);
+    int d = 0;
+    EXPECT(atb_instance_geometry(3, &a, &b, &c, &d) == ATB_OK && a == 1 && b == 2 && c == 6 && d == 32);
+    EXPECT(atb_instance_geometry(0, nullptr, nullptr, nullptr, &d) == ATB_OK && d == 16);
+    EXPECT(atb_instance_geometry(9, &a, &b, &c, &d) == ATB_ERR_INVALID_ARG);
 
     atb_bfp16_layout_t lay;
     EXPECT(atb_bfp16_layout(3000, 4104, &lay) == ATB_OK && lay.panels == 65 && lay.man_stride == 3000 * 64);
@@ -152,10 +154,11 @@ static void api_paths()
     EXPECT(atb_bfp16_decode(fake, nullptr, 1, 8, nullptr) == ATB_ERR_INVALID_ARG);
 
     double flop = 0;
-    EXPECT(atb_mfma_probe(nullptr, nullptr, 1, 1, 1, nullptr, &flop) == ATB_ERR_INVALID_ARG);
-    EXPECT(atb_mfma_probe(fake, nullptr, 0, 1, 1, nullptr, &flop) == ATB_ERR_INVALID_ARG);
-    EXPECT(atb_mfma_probe(fake, fake + 4, 1, 1, 1, nullptr, &flop) == ATB_ERR_INVALID_ARG);          // clocks misaligned
-    EXPECT(atb_mfma_probe(fake, nullptr, 2, 3, 1, nullptr, &flop) == ATB_ERR_HIP && flop == 8.0 * 2 * 3 * 32 * 32768.0);
+    EXPECT(atb_mfma_probe(nullptr, nullptr, 1, 1, 1, 16, nullptr, &flop) == ATB_ERR_INVALID_ARG);
+    EXPECT(atb_mfma_probe(fake, nullptr, 0, 1, 1, 16, nullptr, &flop) == ATB_ERR_INVALID_ARG);
+    EXPECT(atb_mfma_probe(fake, fake + 4, 1, 1, 1, 16, nullptr, &flop) == ATB_ERR_INVALID_ARG);          // clocks misaligned
+    EXPECT(atb_mfma_probe(fake, nullptr, 1, 1, 1, 8, nullptr, &flop) == ATB_ERR_INVALID_ARG);                // no such MFMA form
+    EXPECT(atb_mfma_probe(fake, nullptr, 2, 3, 1, 32, nullptr, &flop) == ATB_ERR_HIP && flop == 8.0 * 2 * 3 * 32 * 32768.0);
 }
 
 static void model_paths()
@@ -193,10 +196,11 @@ static void model_paths()
     EXPECT(atb_select_tiles(64, 64, 64, &x, ranked.data(), 8, &count) == ATB_OK);
 
     atb_micro_model mm;
-    EXPECT(atb_model_microkernel(256, 256, 64, 256, 2, 4, 1, &mm) == ATB_OK && mm.n_mfma == 256 && mm.mfma_util > 0 && mm.mfma_util <= 1);
-    EXPECT(atb_model_microkernel(256, 256, 64, 256, 2, 4, 1, nullptr) == ATB_ERR_INVALID_ARG);
-    EXPECT(atb_model_microkernel(96, 256, 64, 256, 2, 4, 1, &mm) == ATB_ERR_BAD_TILE);
-    EXPECT(atb_model_microkernel(32, 64, 40, 64, 1, 2, 6, &mm) == ATB_ERR_BAD_TILE);
+    EXPECT(atb_model_microkernel(256, 256, 64, 256, 2, 4, 1, 16, &mm) == ATB_OK && mm.n_mfma == 256 && mm.mfma_util > 0 && mm.mfma_util <= 1);
+    EXPECT(atb_model_microkernel(256, 256, 64, 256, 2, 4, 1, 16, nullptr) == ATB_ERR_INVALID_ARG);
+    EXPECT(atb_model_microkernel(256, 256, 64, 256, 2, 4, 1, 8, &mm) == ATB_ERR_INVALID_ARG);
+    EXPECT(atb_model_microkernel(96, 256, 64, 256, 2, 4, 1, 16, &mm) == ATB_ERR_BAD_TILE);
+    EXPECT(atb_model_microkernel(32, 64, 40, 64, 1, 2, 6, 32, &mm) == ATB_ERR_BAD_TILE);
 }
 
 int main()

@@ -15,6 +15,7 @@ Instance make(int T_MA, int T_MC, int T_K, int T_N, int wm, int wn, int lds, boo
     i.T_MA = T_MA; i.T_MC = T_MC; i.T_K = T_K; i.T_N = T_N;
     i.wave_m = wm; i.wave_n = wn; i.threads = wm * wn * 64; i.lds_bytes = lds;
     i.wg_per_cu = 160 * 1024 / lds;
+    i.mfma_rows = (wm * wn == 8) ? 16 : 32;
     i.eff_scale = 1.0; i.lone_cap = 0.0;
     i.launch = &no_device;
     i.launch_fmt = fmt ? &no_device_fmt : nullptr;
@@ -37,7 +38,7 @@ int find_instance(int T_MA, int T_MC, int T_K, int T_N)
 }
 hipError_t launch_quantize(const float *, int64_t, int8_t *, uint8_t *, int64_t, int64_t, hipStream_t) { return hipErrorNoDevice; }
 hipError_t launch_decode(const int8_t *, const uint8_t *, uint16_t *, int64_t, int64_t, hipStream_t) { return hipErrorNoDevice; }
-hipError_t launch_mfma_probe(float *, unsigned long long *, int, int, int, hipStream_t) { return hipErrorNoDevice; }
+hipError_t launch_mfma_probe(float *, unsigned long long *, int, int, int, int, hipStream_t) { return hipErrorNoDevice; }
 double mfma_probe_flop(int workgroups, int iters) { return 8.0 * workgroups * iters * 32.0 * 32768.0; }
 size_t mfma_probe_sink_bytes(int workgroups) { return (size_t)workgroups * 512 * 4; }
 }  // namespace atb

@@ -205,8 +205,8 @@ def test_microkernel_model_against_measurements():
         if line.startswith("#") or not line.strip():
             continue
         f = line.split()
-        rows.append((tuple(int(x) for x in f[:4]), tuple(int(x) for x in f[4:7]), float(f[7]),
-                     None if f[8] == "-" else float(f[8]), f[9]))
+        rows.append((tuple(int(x) for x in f[:4]), tuple(int(x) for x in f[4:8]), float(f[8]),
+                     None if f[9] == "-" else float(f[9]), f[10]))
     inst = atb.instances()
     assert {r[0] for r in rows} == set(inst)
     for tiles, geom, tflops, busy, flag in rows:
@@ -222,15 +222,15 @@ def test_microkernel_model_against_measurements():
             if busy is not None:
                 assert abs(m.mfma_util - busy) < 0.10, (tiles, m.mfma_util, busy)
     # every large tile is limited by the VALU issue port (decode next to MFMAs), the small ones by the LDS
-    big = atb.model_microkernel(128, 256, 64, 256, 2, 4, 1)
+    big = atb.model_microkernel(128, 256, 64, 256, 2, 4, 1, 16)
     assert big.valu_cycles > big.mfma_cycles > big.lds_cycles * 0.9 and big.valu_cycles > big.lds_cycles
-    small = atb.model_microkernel(64, 64, 64, 64, 2, 2, 4)
+    small = atb.model_microkernel(64, 64, 64, 64, 2, 2, 4, 16)
     assert small.lds_cycles > small.valu_cycles > small.mfma_cycles
     L = atb.lib()
-    assert L.atb_model_microkernel(128, 256, 64, 256, 2, 4, 1, None) == 1
+    assert L.atb_model_microkernel(128, 256, 64, 256, 2, 4, 1, 16, None) == 1
     mm = atb.MicroModel()
-    assert L.atb_model_microkernel(96, 256, 64, 256, 2, 4, 1, ctypes.byref(mm)) == 2      # rho not an integer
-    assert L.atb_model_microkernel(128, 256, 64, 256, 3, 4, 1, ctypes.byref(mm)) == 2     # bands do not divide
+    assert L.atb_model_microkernel(96, 256, 64, 256, 2, 4, 1, 16, ctypes.byref(mm)) == 2      # rho not an integer
+    assert L.atb_model_microkernel(128, 256, 64, 256, 3, 4, 1, 16, ctypes.byref(mm)) == 2     # bands do not divide
 
 
 def test_host_packers_agree():

@@ -59,7 +59,7 @@ def test_launch_without_a_device_returns_hip_error():
             assert L.atb_last_hip_error() != 0
             L.atb_gemm_destroy(h)
         assert L.atb_bfp16_quantize(vp(base), 8, vp(base), 1, 8, None) == 5
-        assert L.atb_mfma_probe(vp(base), None, 1, 1, 1, None, None) == 5
+        assert L.atb_mfma_probe(vp(base), None, 1, 1, 1, 16, None, None) == 5
         print("no-device ok")
     """ % ROOT)
     env = dict(os.environ, HIP_VISIBLE_DEVICES="", ROCR_VISIBLE_DEVICES="", CUDA_VISIBLE_DEVICES="")
