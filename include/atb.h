@@ -254,7 +254,7 @@ atb_status atb_select_tiles(int64_t M, int64_t N, int64_t K, const atb_hw_params
  * v_mfma_f32_16x16x32_bf16, which cost the same pipe and port cycles.)
  * mfma_util = mfma / kstep; the chip is power-limited under this kernel, the
  * measured clock follows c * mfma_util^-0.617 (capped at 2.4 GHz) with c = 1.339 GHz for
- * instances that multiply with the 32 x 32 x 16 form and 1.457 GHz for the 16 x 16 x 32
+ * instances that multiply with the 32 x 32 x 16 form and 1.45 GHz for the 16 x 16 x 32
  * form, which draws less power per flop, and
  * pred_flops = flop per K-step * CUs / (kstep / clock).
  * Predicts the full-load throughput of the compiled instances within 15 %

@@ -93,14 +93,14 @@ extern "C" void atb_hw_params_mi355x(atb_hw_params *hw)
     hw->buffer_bytes = 160.0 * 1024.0;           // LDS per CU
     hw->acc_bytes = 256.0 * 1024.0;              // 4 waves x 256 accumulator VGPRs x 64 lanes x 4 B
     // Least-squares fit to the measured K-step times of the 256x256x64 instances at rho = 1, 2, 4, 8
-    // on 8192^3 (in cycles of the nominal 2.4 GHz clock): 3744 + 140 rho + 68 / rho, against 2048
-    // cycles of MFMA issue, i.e. Eff_micro(64) = 0.547.  T_K = 128 measured no better than 64, so the
+    // on 8192^3 (in cycles of the nominal 2.4 GHz clock): 3417 + 172 rho + 341 / rho, against 2048
+    // cycles of MFMA issue, i.e. Eff_micro(64) = 0.599.  T_K = 128 measured no better than 64, so the
     // fit saturates early (small eps): Eff_micro ~ 1 / II.
-    hw->delta_cycles = 140.0;
-    hw->fill_cycles = 68.0;
+    hw->delta_cycles = 172.0;
+    hw->fill_cycles = 341.0;
     hw->eta = 1.0;
     hw->eps = 0.4;
-    hw->II = 1.8221;
+    hw->II = 1.6620;
     hw->a_bytes = 1.125;                         // A BFP16: 9 bytes per 8 elements
     hw->b_bytes = 2.0;
     hw->c_bytes = 2.0;
@@ -260,7 +260,7 @@ extern "C" atb_status atb_model_microkernel(int T_MA, int T_MC, int T_K, int T_N
     m.kstep_cycles = m.steady_cycles + rho * m.switch_cycles;
     m.mfma_util = m.mfma_cycles / m.kstep_cycles;
     // the 16 x 16 x 32 form of the MFMA draws less power per flop, which the chip turns into clock
-    m.clock_hz = std::min(2.4e9, (mfma_rows == 16 ? 1.457e9 : 1.339e9) * std::pow(m.mfma_util, -0.617));
+    m.clock_hz = std::min(2.4e9, (mfma_rows == 16 ? 1.45e9 : 1.339e9) * std::pow(m.mfma_util, -0.617));
     m.pred_flops = m.n_mfma * 32768.0 * 256.0 / (m.kstep_cycles / m.clock_hz);
     *out = m;
     return ATB_OK;

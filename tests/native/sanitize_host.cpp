@@ -96,10 +96,10 @@ static void api_paths()
     EXPECT(atb_instance_get(1, nullptr, nullptr, nullptr, nullptr) == ATB_OK);
     EXPECT(atb_instance_get(-1, &a, &b, &c, &d) == ATB_ERR_INVALID_ARG);
     EXPECT(atb_instance_get(4, &a, &b, &c, &d) == ATB_ERR_INVALID_ARG);
-    int d = 0;
-    EXPECT(atb_instance_geometry(3, &a, &b, &c, &d) == ATB_OK && a == 1 && b == 2 && c == 6 && d == 32);
-    EXPECT(atb_instance_geometry(0, nullptr, nullptr, nullptr, &d) == ATB_OK && d == 16);
-    EXPECT(atb_instance_geometry(9, &a, &b, &c, &d) == ATB_ERR_INVALID_ARG);
+    int rows = 0;
+    EXPECT(atb_instance_geometry(3, &a, &b, &c, &rows) == ATB_OK && a == 1 && b == 2 && c == 6 && rows == 32);
+    EXPECT(atb_instance_geometry(0, nullptr, nullptr, nullptr, &rows) == ATB_OK && rows == 16);
+    EXPECT(atb_instance_geometry(9, &a, &b, &c, &rows) == ATB_ERR_INVALID_ARG);
 
     atb_bfp16_layout_t lay;
     EXPECT(atb_bfp16_layout(3000, 4104, &lay) == ATB_OK && lay.panels == 65 && lay.man_stride == 3000 * 64);
