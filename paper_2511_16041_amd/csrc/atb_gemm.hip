@@ -50,7 +50,7 @@ typedef short shortx4 __attribute__((ext_vector_type(4)));
 // Sign-extended byte `byte` of word w as float (one v_cvt_f32_i32 with a byte select).
 ATB_DEV float mant_to_float(int w, int byte) { return (float)(int)(signed char)(w >> (8 * byte)); }
 
-template <int T_MA_, int T_MC_, int T_K_, int T_N_, int WM_, int WN_, int PF_, int AB_ = 2, int AO_ = -1, int BO_ = 0, int KU_ = 2, int NB_ = 2, int HW_ = 0, int SKEW_ = 0, int MB_ = 0>
+template <int T_MA_, int T_MC_, int T_K_, int T_N_, int WM_, int WN_, int PF_, int AB_ = 2, int AO_ = -1, int BO_ = 0, int KU_ = 2, int NB_ = 2, int HW_ = 0, int SKEW_ = 0, int MB_ = 0, int OCC_ = 1>
 struct Shape {
     static constexpr int T_MA = T_MA_, T_MC = T_MC_, T_K = T_K_, T_N = T_N_, WM = WM_, WN = WN_;
     static constexpr int PF = PF_;                // A sub-tiles fetched this many phases ahead of their use
@@ -91,6 +91,10 @@ struct Shape {
     // and their operand reads without gaps (measured 10-20 % slower with MB = 16), unless the instance says otherwise.
     // A 32-row band of A is HB row blocks of MB rows.
     static constexpr int MB = MB_ ? MB_ : (WM * WN == 8 ? 16 : 32);
+    // Waves per SIMD that the kernel is compiled for (the second argument of __launch_bounds__: the register
+    // allocator then stays within 512 / OCC registers, spilling if it must).  Set where a few registers too many
+    // would cost a whole workgroup per CU.
+    static constexpr int OCC = OCC_;
     static constexpr int KM = 512 / MB;           // k per MFMA
     static constexpr int HB = 32 / MB;            // row blocks per band
     static constexpr int NC = T_N / MB / WN;      // column blocks per wave
@@ -1261,7 +1265,7 @@ __device__ __forceinline__ void tile_loop(const GemmParams &p, char *lds)
 }
 
 template <class S, bool VEC, bool BBFP = false, bool CBFP = false, bool BTR = false>
-__global__ void __launch_bounds__(S::NT) atb_gemm_kernel(const GemmParams p)
+__global__ void __launch_bounds__(S::NT, S::OCC) atb_gemm_kernel(const GemmParams p)
 {
     __shared__ __attribute__((aligned(16))) char lds[BBFP ? S::LDS_BYTES_BT : S::LDS_BYTES];
     if constexpr (S::HW > 0) {
@@ -1366,6 +1370,7 @@ Instance make_instance(double eff_scale = 0.0, double lone_cap = 0.0)
     // workgroups that share a CU: one for the 8-wave workgroups (two waves per SIMD that use more than a quarter of
     // the SIMD's registers each); for the others what the LDS footprint and the 8 wave slots of a SIMD admit
     i.wg_per_cu = (S::CW == 8) ? 1 : std::max(1, std::min(std::min(8, (160 * 1024) / S::LDS_BYTES), 8 * 256 / S::NT));
+    if (S::OCC > 1) i.wg_per_cu = std::min(i.wg_per_cu, S::OCC * 256 / S::NT);      // compiled for OCC waves per SIMD: no more fit by registers
     i.mfma_rows = S::MB;
     i.launch = &launch_instance<S>;
     if constexpr (FMT) i.launch_fmt = &launch_instance_fmt<S>; else i.launch_fmt = nullptr;
@@ -1444,7 +1449,10 @@ const Instance g_instances[] = {
     // 128 x 128 on a 2 x 2 grid of multiplying waves plus 4 helper waves that stage (last argument); two and
     // three workgroups per CU.  Helper waves: 920 -> 1016 TFLOP/s at 8192^3, 343-369 -> 439-514 at M = 1024, N = 2048.
     make_instance<Shape<128, 128, 64, 128, 2, 2, 2, 2, -1, 0, 2, 2, 4>, true>(),
-    make_instance<Shape<64, 128, 64, 128, 2, 2, 4, 2, -1, 0, 2, 2, 4>, true>(),
+    // (the ATB one multiplies with 16 x 16 x 32 MFMAs, compiled for 128 registers so that two workgroups still share
+    // a CU: +3 % on 8192^3, +6 % at M = N = 2048; the symmetric one needs 10 registers more and loses far more to
+    // spills than the MFMA form returns, so it keeps 32 x 32 x 16)
+    make_instance<Shape<64, 128, 64, 128, 2, 2, 4, 2, -1, 0, 2, 2, 4, 0, 16, 4>, true>(),
 #endif
 #if ATB_IN_GROUP(2)
     // 64 x 128 with T_K = 128 (one workgroup per CU): the instance for problems with about one such tile per CU
