@@ -50,7 +50,7 @@ typedef short shortx4 __attribute__((ext_vector_type(4)));
 // Sign-extended byte `byte` of word w as float (one v_cvt_f32_i32 with a byte select).
 ATB_DEV float mant_to_float(int w, int byte) { return (float)(int)(signed char)(w >> (8 * byte)); }
 
-template <int T_MA_, int T_MC_, int T_K_, int T_N_, int WM_, int WN_, int PF_, int AB_ = 2, int AO_ = -1, int BO_ = 0, int KU_ = 2, int NB_ = 2, int HW_ = 0, int SKEW_ = 0, int MB_ = 0, int OCC_ = 1>
+template <int T_MA_, int T_MC_, int T_K_, int T_N_, int WM_, int WN_, int PF_, int AB_ = 2, int AO_ = -1, int BO_ = 0, int KU_ = 2, int NB_ = 2, int HW_ = 0, int SKEW_ = 0, int MB_ = 0, int OCC_ = 1, bool ADMA_ = false>
 struct Shape {
     static constexpr int T_MA = T_MA_, T_MC = T_MC_, T_K = T_K_, T_N = T_N_, WM = WM_, WN = WN_;
     static constexpr int PF = PF_;                // A sub-tiles fetched this many phases ahead of their use
@@ -122,7 +122,19 @@ struct Shape {
     static constexpr int PB = T_N * 2;            // B rows are not padded: an XOR swizzle of the 16-byte chunks avoids the bank conflicts
     static constexpr int A_BYTES = T_MA * PA;
     static constexpr int B_BYTES = T_K * PB;
-    static constexpr int LDS_BYTES = AB * A_BYTES + NB * B_BYTES;
+    // ADMA: the A sub-tiles reach the CU as B does, requested by the second wave group straight into LDS -- as they
+    // lie in memory, 64 mantissa bytes and 8 exponent bytes per row (the K-panel-major planes make a sub-tile's share
+    // of a K-step one contiguous run of each) -- into a ring of NR raw buffers; the decoding waves read their chunks
+    // from there instead of from memory.  Loads that return into the registers of the decoding waves cost this
+    // kernel more than any other part of its side work (power, and waits in the very waves the K-step waits for);
+    // as requests of the other group, which has little else to do, they cost a fraction of that.  The ring is what
+    // ATB's smaller A buffers pay for: 36 KiB at T_MA = 128, which does not fit next to a symmetric 256-row tile
+    // (its ring would be 72 KiB; even two raw buffers, 36 KiB, put it at 164 KiB).
+    static constexpr bool ADMA = ADMA_;
+    static constexpr int NR = 4;                                   // raw buffers: sub-tile g uses buffer g % NR
+    static constexpr int RAW_BYTES = T_MA * (kPanelK + kPanelK / 8);
+    static constexpr int RAW_RING = ADMA ? NR * RAW_BYTES : 0;
+    static constexpr int LDS_BYTES = AB * A_BYTES + NB * B_BYTES + RAW_RING;
     // B given as BFP16 (B^T, N x K, blocks along K): the tile is staged like A, [n][k] with pitch PA
     static constexpr int BT_BYTES = T_N * PBF;
     static constexpr int LDS_BYTES_BT = AB * A_BYTES + 2 * BT_BYTES;
@@ -168,6 +180,8 @@ struct Shape {
     static_assert(AO >= 0 && AO <= A_SLABS && BO >= 0 && BO <= B_SLABS, "staging split");
     static_assert(B_CPR >= 8, "the B swizzle needs 8 chunks per row");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 CU");
+    static_assert(!ADMA || (WM * WN == 8 && HW == 0 && T_K == kPanelK && T_MA == 128 && AB == 2 && PF == 2 && (KU * (T_MC / T_MA)) % NR == 0),
+                  "raw A staging: two wave groups, one K-panel per K-step, one KiB of mantissas per wave and request, static ring indices");
     static_assert((MTW + SKEW) * HB * NC * ACC <= 256, "C tile must fit the accumulator registers");
     static_assert(SKEW == 0 || (CW == 8 && WM == 2 && HW == 0 && AB == 2 && SKEW < MTW), "the uneven deal is between the two wave groups of a 2 x 4 grid");
 };
@@ -181,6 +195,7 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 struct Rsrc {
     __amdgpu_buffer_rsrc_t am, ae, b, bm, be;
     intx4 b_words;      // the B descriptor once more as four dwords, for the hand-issued requests of the symmetric instances
+    intx4 am_words, ae_words;   // likewise the A descriptors, for the raw requests (ADMA)
 };
 
 constexpr int kRsrcFlags = 0x00020000;           // raw buffer, 32-bit data format
@@ -270,7 +285,12 @@ struct TileKernel {
     static constexpr int NPAIR = APT * ACE / 2;                                          // mantissa pairs per thread per sub-tile
     // A thread with two 16-mantissa chunks takes them side by side in one row (32 consecutive k): their
     // four exponent bytes are one aligned dword, so one exponent request serves both chunks.
-    static constexpr bool PAIRK = (APT == 2 && ACE == 16 && A_FIRST == 0 && S::T_K == 64);
+    // Raw A staging through LDS (Shape::ADMA): ROLE 2 requests the sub-tiles, ROLE 1 reads its chunks from the raw ring.
+    static constexpr bool ADMA_ON = S::ADMA && VEC && !BBFP && !SK && (ROLE == 1 || ROLE == 2);
+    static constexpr int RQM = S::T_MA / 64;                 // 1 KiB mantissa requests per wave of the group and sub-tile
+    static constexpr int RQ = (ADMA_ON && ROLE == 2) ? RQM + 1 : 0;   // ... plus one 256-byte request for the exponents
+    static constexpr int RAW_LEAD = S::PF + 2;               // sub-tile x is requested in phase x - RAW_LEAD, complete one phase later, read in phase x - PF
+    static constexpr bool PAIRK = (APT == 2 && ACE == 16 && A_FIRST == 0 && S::T_K == 64 && !ADMA_ON);
     static constexpr int A_VMEM = PAIRK ? 3 : APT * 2;       // memory requests per thread and A sub-tile
     // Rows >= M of an edge tile only feed rows of C that are never stored.  SK is the variant of the kernel
     // for tiles at least half of whose rows lie beyond M (skinny problems, where that is most of the VALU
@@ -326,6 +346,13 @@ struct TileKernel {
     // size down, so the hardware range check keeps masking panels past the last of A and rows >= K of B, and no
     // vector register that a memory instruction has just read is written right after it.
     int a_moff[S::RHO][APTN], a_eoff[S::RHO][APTN], b_off[BPTN];
+    // ADMA, ROLE 2: byte offsets of this lane's raw requests (mantissas: request e of sub-tile sub; exponents) in the
+    // planes, relative to the K-step the A descriptors point at; LDS address of this wave's first mantissa request
+    // and of its exponent request in raw buffer 0.  ROLE 1: where this thread reads its first chunk and its exponent
+    // dword in raw buffer 0 (chunk i: 4 KiB / 512 bytes further on).
+    int raw_moff[S::RHO][RQM], raw_eoff[S::RHO];
+    char *raw_req_m, *raw_req_e;
+    const char *raw_rd_m, *raw_rd_e;
     const int8_t *am_ptr;              // start of the K-step the next A fetch belongs to
     const uint8_t *ae_ptr;
     const uint16_t *b_ptr;             // start of the K-step the next B fetch belongs to
@@ -504,12 +531,30 @@ struct TileKernel {
             for (int b = 0; b < S::HB * S::NC; ++b)
 #pragma unroll
                 for (int v = 0; v < S::ACC; ++v) acc[a][b / S::NC][b % S::NC][v] = 0.0f;
+        if constexpr (ADMA_ON) {
+            char *raw_base = lds + S::AB * S::A_BYTES + S::NB * S::B_BYTES;
+            const int w = __builtin_amdgcn_readfirstlane(wave & 3);
+            // a sub-tile's T_MA x 64 mantissa bytes are one contiguous run of the plane, cut into 1 KiB requests that
+            // the four waves of the group take in turn; its T_MA x 8 exponent bytes are four requests of 256 bytes
+            raw_req_m = raw_base + w * 1024;
+            raw_req_e = raw_base + S::T_MA * kPanelK + w * 256;
+#pragma unroll
+            for (int sub = 0; sub < S::RHO; ++sub) {
+#pragma unroll
+                for (int e = 0; e < RQM; ++e) raw_moff[sub][e] = sub * S::T_MA * kPanelK + (e * 4 + w) * 1024 + lane * 16;
+                raw_eoff[sub] = sub * S::T_MA * (kPanelK / 8) + w * 256 + lane * 4;
+            }
+            // chunk c = i * NTS + stid of the sub-tile is row c / 4, 16 mantissas from 16 (c % 4): byte 16 c of the raw
+            // mantissas (consecutive lanes, consecutive 16 bytes); its two exponents sit in dword (c % 4) / 2 of the row's 8
+            raw_rd_m = raw_base + stid * 16;
+            raw_rd_e = raw_base + S::T_MA * kPanelK + (stid / 4) * (kPanelK / 8) + ((stid % 4) / 2) * 4;
+        }
         // the offsets above are those of the tile at row 0, column 0; the streams move them to their tiles
         a_m0 = 0;
         b_n0 = 0;
         c_t = t_first;
         tile_at(c_t, m0, n0);
-        if constexpr (APT > 0) { open_a(t_first); remake_a(); }
+        if constexpr ((APT > 0 && !ADMA_ON) || RQ > 0) { open_a(t_first); remake_a(); }
         a_mask = 0xFFFFFFFFu;
         if constexpr (SK) {
             const int wrow = __builtin_amdgcn_readfirstlane(a_row);     // smallest staging row of this wave
@@ -547,6 +592,14 @@ struct TileKernel {
                     a_moff[sub][i] += d * kPanelK;
                     a_eoff[sub][i] += d * (kPanelK / 8);
                 }
+            if constexpr (RQ > 0) {
+#pragma unroll
+                for (int sub = 0; sub < S::RHO; ++sub) {
+#pragma unroll
+                    for (int e = 0; e < RQM; ++e) raw_moff[sub][e] += d * kPanelK;
+                    raw_eoff[sub] += d * (kPanelK / 8);
+                }
+            }
             am_left = p.k_panels * p.M * kPanelK;
             ae_left = p.k_panels * p.M * (kPanelK / 8);
             a_steps = kt_steps;
@@ -602,8 +655,71 @@ struct TileKernel {
 
     ATB_DEV void remake_a()
     {
-        rs.am = make_rsrc(am_ptr, am_left);
-        rs.ae = make_rsrc(ae_ptr, ae_left);
+        if constexpr (RQ > 0) {
+            const uint64_t m = reinterpret_cast<uint64_t>(am_ptr), e = reinterpret_cast<uint64_t>(ae_ptr);
+            rs.am_words = intx4{__builtin_amdgcn_readfirstlane((int)(uint32_t)m), __builtin_amdgcn_readfirstlane((int)(uint32_t)(m >> 32) & 0xFFFF),
+                                __builtin_amdgcn_readfirstlane(am_left), kRsrcFlags};
+            rs.ae_words = intx4{__builtin_amdgcn_readfirstlane((int)(uint32_t)e), __builtin_amdgcn_readfirstlane((int)(uint32_t)(e >> 32) & 0xFFFF),
+                                __builtin_amdgcn_readfirstlane(ae_left), kRsrcFlags};
+        } else {
+            rs.am = make_rsrc(am_ptr, am_left);
+            rs.ae = make_rsrc(ae_ptr, ae_left);
+        }
+    }
+
+    // The A request stream moves on by one K-step (or to the workgroup's next tile) and rebuilds its descriptors.
+    ATB_DEV void advance_a()
+    {
+        if (--a_steps == 0) {
+            open_a(a_t + t_stride);
+        } else {
+            am_ptr += (S::T_K / kPanelK) * p.M * kPanelK;
+            ae_ptr += (S::T_K / kPanelK) * p.M * (kPanelK / 8);
+            am_left = max(am_left - (S::T_K / kPanelK) * p.M * kPanelK, 0);
+            ae_left = max(ae_left - (S::T_K / kPanelK) * p.M * (kPanelK / 8), 0);
+        }
+        remake_a();
+    }
+
+    // ADMA, ROLE 2: request e of sub-tile `sub` of the K-step the A descriptors point at, straight into raw buffer
+    // `slot` (e < RQM: 1 KiB of mantissas; e == RQM: this wave's 256 bytes of exponents).  Hand-issued like the B
+    // requests (see load_b_chunk).  After the last request of the K-step's last sub-tile the descriptors move on.
+    template <int slot, int sub, int e>
+    ATB_DEV void load_raw_chunk()
+    {
+#if defined(__HIP_DEVICE_COMPILE__)
+        int m0_saved;
+        if constexpr (e < RQM) {
+            const unsigned lds_addr = (unsigned)reinterpret_cast<uintptr_t>(raw_req_m + slot * S::RAW_BYTES + e * 4096);
+            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, 0 offen lds\n\ts_mov_b32 m0, %0"
+                         : "=&s"(m0_saved)
+                         : "s"(__builtin_amdgcn_readfirstlane((int)lds_addr)), "v"(raw_moff[sub][e]), "s"(rs.am_words) : "memory");
+        } else {
+            const unsigned lds_addr = (unsigned)reinterpret_cast<uintptr_t>(raw_req_e + slot * S::RAW_BYTES);
+            asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tbuffer_load_dword %2, %3, 0 offen lds\n\ts_mov_b32 m0, %0"
+                         : "=&s"(m0_saved)
+                         : "s"(__builtin_amdgcn_readfirstlane((int)lds_addr)), "v"(raw_eoff[sub]), "s"(rs.ae_words) : "memory");
+        }
+#endif
+        if constexpr (sub == S::RHO - 1 && e == RQM) advance_a();
+    }
+
+    template <int x, int e = 0>
+    ATB_DEV void load_raw()        // prologue: all requests of sub-tile x
+    {
+        if constexpr (e < RQ) {
+            load_raw_chunk<x % S::NR, x % S::RHO, e>();
+            load_raw<x, e + 1>();
+        }
+    }
+
+    template <int x = 0>
+    ATB_DEV void load_raw_first()
+    {
+        if constexpr (x < RAW_LEAD) {
+            load_raw<x>();
+            load_raw_first<x + 1>();
+        }
     }
 
     // a K-step's offsets stay below 2^31, so a longer remainder may be cut off there
@@ -655,9 +771,15 @@ struct TileKernel {
 
     // Chunk i of sub-tile `sub` of the K-step the A descriptors point at, into register set `set`.
     // After the last chunk of the last sub-tile the descriptors move on to the next K-step.
-    template <int set, int sub, int i>
+    // ADMA (ROLE 1): the chunk comes from raw buffer `slot` in LDS instead; the request stream is the other group's.
+    template <int set, int sub, int i, int slot = 0>
     ATB_DEV void load_a_chunk()
     {
+        if constexpr (ADMA_ON) {
+            a_mant[set][i] = *reinterpret_cast<const intx4 *>(raw_rd_m + slot * S::RAW_BYTES + i * (NTS * 16));
+            a_expo[set][i] = *reinterpret_cast<const unsigned *>(raw_rd_e + slot * S::RAW_BYTES + i * (NTS / 4) * (kPanelK / 8));
+            return;
+        }
         if constexpr (ACE == 16) {
             a_mant[set][i] = __builtin_amdgcn_raw_buffer_load_b128(rs.am, a_moff[sub][i], 0, 0);
         } else {
@@ -667,24 +789,14 @@ struct TileKernel {
         // the aligned dword that holds this chunk's exponent byte(s): sub-dword loads are far slower
         if constexpr (!PAIRK || i == 0)
             a_expo[set][i] = __builtin_amdgcn_raw_buffer_load_b32(rs.ae, a_eoff[sub][i], 0, 0);
-        if constexpr (sub == S::RHO - 1 && i == APT - 1) {
-            if (--a_steps == 0) {
-                open_a(a_t + t_stride);
-            } else {
-                am_ptr += (S::T_K / kPanelK) * p.M * kPanelK;
-                ae_ptr += (S::T_K / kPanelK) * p.M * (kPanelK / 8);
-                am_left = max(am_left - (S::T_K / kPanelK) * p.M * kPanelK, 0);
-                ae_left = max(ae_left - (S::T_K / kPanelK) * p.M * (kPanelK / 8), 0);
-            }
-            remake_a();
-        }
+        if constexpr (sub == S::RHO - 1 && i == APT - 1) advance_a();
     }
 
     template <int set, int sub, int i = 0>
     ATB_DEV void load_a()
     {
         if constexpr (i < APT) {
-            load_a_chunk<set, sub, i>();
+            load_a_chunk<set, sub, i, set % S::NR>();      // (prologue: sub-tile `set`, raw buffer `set`)
             load_a<set, sub, i + 1>();
         }
     }
@@ -938,7 +1050,7 @@ struct TileKernel {
     template <int s>
     static constexpr int n_side()
     {
-        return APT + (s == 0 ? BPT + BTPT : 0) + NSTEP_A + NSTEP_B + ((!VEC && s + 1 == S::RHO) ? BPT : 0);
+        return RQ + APT + (s == 0 ? BPT + BTPT : 0) + NSTEP_A + NSTEP_B + ((!VEC && s + 1 == S::RHO) ? BPT : 0);
     }
 
     template <int ki, int s, int j>
@@ -947,13 +1059,17 @@ struct TileKernel {
         constexpr int kpar = ki & 1;             // parity of the K-step: B buffers and B register sets
         constexpr int g = ki * S::RHO + s;       // running sub-tile index within the loop body
         constexpr int n_la = APT, n_lb = (s == 0 ? BPT : 0), n_lt = (s == 0 ? BTPT : 0), n_dt = NPAIR_B / S::RHO;
-        constexpr int j1 = n_lb, j2 = j1 + n_lt, j3 = j2 + n_la, j4 = j3 + NSTEP_A, j5 = j4 + NSTEP_B;
-        if constexpr (j < j1) {
-            load_b_chunk<j>(kpar);
+        // (the raw A requests come first: they are awaited a phase later, the B tile's only three phases later, and
+        // requests complete in order)
+        constexpr int j0 = RQ, j1 = j0 + n_lb, j2 = j1 + n_lt, j3 = j2 + n_la, j4 = j3 + NSTEP_A, j5 = j4 + NSTEP_B;
+        if constexpr (j < j0) {
+            load_raw_chunk<(g + RAW_LEAD) % S::NR, (s + RAW_LEAD) % S::RHO, j>();
+        } else if constexpr (j < j1) {
+            load_b_chunk<j - j0>(kpar);
         } else if constexpr (j < j2) {
             load_bt_chunk<kpar ^ 1, j - j1>();
         } else if constexpr (j < j3) {
-            load_a_chunk<g % S::PF, (s + S::PF) % S::RHO, j - j2>();
+            load_a_chunk<g % S::PF, (s + S::PF) % S::RHO, j - j2, (g + S::PF) % S::NR>();
         } else if constexpr (j < j4) {
             if constexpr (SK)
                 decode_block<(g + S::DA) % S::PF, j - j3>(a_wr[(g + S::DA) % S::AB], a_mask >> (((s + S::DA) % S::RHO) * APTN));
@@ -1054,7 +1170,10 @@ struct TileKernel {
             // last-but-one phase of K-step kt + 1; younger are the A requests of NB rho - 1 phases and
             // NB - 1 further B tiles.  (A smaller count only waits for more than necessary.)
             if constexpr (VEC && BPT > 0 && S::RHO == 1) wait_vm<vm_cap((S::NB - 1) * A_VMEM + (S::NB - 2) * BPT)>();
-            if constexpr (VEC && BPT > 0 && S::RHO >= 2 && s == S::RHO - 2)
+            // ADMA: the raw sub-tile requested in the previous phase is read by the other group in the next one, so
+            // everything older than this phase's own requests has to have landed (which covers the B tile as well)
+            if constexpr (RQ > 0) wait_vm<vm_cap(RQ + BPT)>();
+            else if constexpr (VEC && BPT > 0 && S::RHO >= 2 && s == S::RHO - 2)
                 wait_vm<vm_cap((S::NB * S::RHO - 1) * A_VMEM + (S::NB - 1) * BPT)>();
             switch_barrier();   // the "kernel switch" of the ATB nest
             phases<ki, s + 1>();
@@ -1094,6 +1213,12 @@ struct TileKernel {
         // prologue: the first NB B tiles into LDS, the first PF A sub-tiles into registers, sub-tile 0
         // into LDS, B tile 0 into fragment registers
         if constexpr (S::NB > 2) b_fill_off = 0;
+        if constexpr (ADMA_ON) {
+            // the first RAW_LEAD raw sub-tiles into the ring, landed and published before the decoding group reads them
+            if constexpr (RQ > 0) load_raw_first();
+            wait_vm<0>();
+            __syncthreads();
+        }
         load_b(0);
         if constexpr (BBFP) { load_bt<0>(); load_bt<1>(); }
         prologue_loads();
@@ -1405,6 +1530,14 @@ Instance make_instance(double eff_scale = 0.0, double lone_cap = 0.0)
 #ifndef ATB_ATB_SKEW
 #define ATB_ATB_SKEW 0
 #endif
+// A third use of the LDS that ATB frees at the 256 x 256 tile: a ring of four raw A sub-tiles (36 KiB at rho = 2)
+// that the second wave group fills with requests straight into LDS, as it does for B, so that the decoding waves
+// read their chunks from LDS instead of loading them from memory into registers (Shape::ADMA).  Parity-green and
+// bit-equal; measured on 8192^3: -0.5 % (1261 against 1268 TFLOP/s, interleaved timing, the same clock): what the A
+// loads cost is the bytes that come into the CU, whichever way they take.  Build option -DATB_ATB_RAW_RING=1.
+#ifndef ATB_ATB_RAW_RING
+#define ATB_ATB_RAW_RING 0
+#endif
 
 const Instance g_instances[] = {
 #if ATB_IN_GROUP(0)
@@ -1426,7 +1559,7 @@ const Instance g_instances[] = {
     // A ring: -3.8 % / -1.6 % at rho = 2 / 4): B tiles already arrive two K-steps after their request, and the
     // deeper A ring costs registers.  Both stay build options (-DATB_ATB_B_RING=3, -DATB_ATB_A_RING=4) for that
     // measurement; the library ships with 2 and 2.
-    make_instance<Shape<128, 256, 64, 256, 2, 4, (ATB_ATB_A_RING == 4 ? 4 : 2), ATB_ATB_A_RING, 2, 0, 2, ATB_ATB_B_RING, 0, ATB_ATB_SKEW>, true>(1.0),
+    make_instance<Shape<128, 256, 64, 256, 2, 4, (ATB_ATB_A_RING == 4 ? 4 : 2), ATB_ATB_A_RING, 2, 0, 2, ATB_ATB_B_RING, 0, ATB_ATB_SKEW, 0, 1, (ATB_ATB_RAW_RING != 0 && ATB_ATB_A_RING == 2)>, true>(1.0),
     make_instance<Shape<64, 256, 64, 256, 2, 4, 4, ATB_ATB_A_RING, 1, 0, 2, ATB_ATB_B_RING>, true>(1.0),
     make_instance<Shape<32, 256, 64, 256, 1, 4, 8, 4>>(1.0),
     // T_K = 128 exists only with ATB: at rho = 8 the A buffers take 17 KiB next to 128 KiB of B; the
