@@ -240,7 +240,7 @@ atb_status atb_select_tiles(int64_t M, int64_t N, int64_t K, const atb_hw_params
  * (Eq. 10).  This is the same decomposition for one gfx950 CU, with unit costs
  * measured on MI355X (csrc/microbench/unit_costs.hip): per C tile and K-step,
  * in shader-clock cycles,
- *   mfma   = n_mfma * 32 / 4                    matrix pipes (8-pass MFMA, 4 SIMDs)
+ *   mfma   = n_mfma * 32 / 4                    matrix pipes (32 cycles per unit of 32768 flop, 4 SIMDs)
  *   valu   = (n_mfma * 17 + n_decode * 6.5 + n_addr * 4) / 4
  *                                               VALU issue ports: an MFMA blocks its SIMD's port for
  *                                               17 of its 32 cycles; a decode instruction costs 6.5
