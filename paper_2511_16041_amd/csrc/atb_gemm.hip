@@ -85,10 +85,11 @@ struct Shape {
     // The MFMA.  gfx950 has two bf16 forms of the same peak rate: 32 x 32 x 16 (rows x columns x k per instruction)
     // and 16 x 16 x 32.  The first needs half as many operand registers and instructions per flop; the second is the
     // cheaper one in power, and this chip is power-limited: an MFMA-only loop on random bf16 operands sustains
-    // 1.92 PFLOP/s with 16 x 16 x 32 against 1.72 with 32 x 32 x 16.  MB = 16 where two waves of the workgroup share a
-    // SIMD (the other wave's instructions fill the gaps between the short MFMAs: +2-3 % on 8192^3), MB = 32 where a
-    // SIMD has one multiplying wave per workgroup, whose single instruction stream cannot issue twice as many MFMAs
-    // and their operand reads without gaps (measured 10-20 % slower with MB = 16), unless the instance says otherwise.
+    // 2.07 PFLOP/s with 16 x 16 x 32 against 1.83 with 32 x 32 x 16.  MB = 16 where two waves of the workgroup share a
+    // SIMD (the other wave's instructions fill the gaps between the short MFMAs: +2 to +6 % on 8192^3, box to box),
+    // MB = 32 where a SIMD has one multiplying wave per workgroup, whose single instruction stream cannot issue twice
+    // as many MFMAs and their operand reads without gaps (rho = 8: 10 % slower with MB = 16), unless the instance
+    // says otherwise.  The two forms give bit-equal results.
     // A 32-row band of A is HB row blocks of MB rows.
     static constexpr int MB = MB_ ? MB_ : (WM * WN == 8 ? 16 : 32);
     // Waves per SIMD that the kernel is compiled for (the second argument of __launch_bounds__: the register
@@ -125,11 +126,10 @@ struct Shape {
     // ADMA: the A sub-tiles reach the CU as B does, requested by the second wave group straight into LDS -- as they
     // lie in memory, 64 mantissa bytes and 8 exponent bytes per row (the K-panel-major planes make a sub-tile's share
     // of a K-step one contiguous run of each) -- into a ring of NR raw buffers; the decoding waves read their chunks
-    // from there instead of from memory.  Loads that return into the registers of the decoding waves cost this
-    // kernel more than any other part of its side work (power, and waits in the very waves the K-step waits for);
-    // as requests of the other group, which has little else to do, they cost a fraction of that.  The ring is what
-    // ATB's smaller A buffers pay for: 36 KiB at T_MA = 128, which does not fit next to a symmetric 256-row tile
-    // (its ring would be 72 KiB; even two raw buffers, 36 KiB, put it at 164 KiB).
+    // from there instead of from memory, and issue no memory instruction at all.  The ring is what ATB's smaller A
+    // buffers pay for: 36 KiB at T_MA = 128, which does not fit next to a symmetric 256-row tile (its ring would be
+    // 72 KiB; even two raw buffers, 36 KiB, put it at 164 KiB).  Measured: the decoding waves wait less, the
+    // throughput does not change (the bytes cost the same whichever way they come in); an experiment, off by default.
     static constexpr bool ADMA = ADMA_;
     static constexpr int NR = 4;                                   // raw buffers: sub-tile g uses buffer g % NR
     static constexpr int RAW_BYTES = T_MA * (kPanelK + kPanelK / 8);
