@@ -80,7 +80,12 @@ typedef struct atb_gemm atb_gemm; /* opaque plan, HOST memory */
  * (M * round_up(K, 64), K * N, M * N; also N * round_up(K, 64) and
  * M * round_up(N, 64) for the BFP16 forms of B and C), and
  * 2 * N * (T_K + 1) < 2^31.
- * On success *out is a new plan, else *out = NULL. */
+ * On success *out is a new plan, else *out = NULL.
+ * Environment (read here, both optional): ATB_LOG=1 prints the plan to
+ * stderr; ATB_GROUP_M=<tile rows, 1..65536> overrides the height of the
+ * patch of C tiles that the workgroups resident on one XCD cover (the
+ * order in which tiles are walked, a measurement aid: results are the same
+ * for every value). */
 atb_status atb_gemm_create(atb_gemm **out, int64_t M, int64_t N, int64_t K,
                            int T_MA, int T_MC, int T_K, int T_N);
 

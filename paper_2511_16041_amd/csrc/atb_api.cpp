@@ -165,6 +165,12 @@ extern "C" atb_status atb_gemm_create_fmt(atb_gemm **out, int64_t M, int64_t N, 
     // so that the result can be the BFP16 operand of a following GEMM as it is
     if (c_format == ATB_FMT_BFP16) p.tiles_n = (int)((atb::round_up(N, atb::kPanelK) + T_N - 1) / T_N);
     p.group_m = (int)std::max<int64_t>(1, 2048 / T_MC);   // an XCD's patch of C tiles is 2048 rows high
+    // measurement aid: ATB_GROUP_M=<tile rows> overrides the height of the patch, so that the counters can
+    // be read with the tiles resident on an XCD laid out as one row (1) or one column (>= 32) of C tiles
+    if (const char *gm = std::getenv("ATB_GROUP_M"); gm && gm[0]) {
+        const long v = std::strtol(gm, nullptr, 10);
+        if (v >= 1 && v <= 65536) p.group_m = (int)v;   // anything else is ignored
+    }
     if (const char *log = std::getenv("ATB_LOG"); log && log[0] == '1') {
         const atb::Instance &x = atb::instance(idx);
         std::fprintf(stderr, "atb_gemm_create: M=%lld N=%lld K=%lld T_MA=%d T_MC=%d T_K=%d T_N=%d rho=%d b=%s c=%s "
