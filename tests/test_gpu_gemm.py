@@ -187,6 +187,24 @@ def test_tile_chain_lengths(tiles, shape):
     _check(_run(mant, expo, Bb, tiles), C_ref, T, f"chain {shape} {tiles}")
 
 
+@pytest.mark.parametrize("tiles", [(256, 256, 64, 256), (64, 128, 64, 128), (32, 64, 64, 64)])
+def test_tile_walk_order_does_not_change_the_result(tiles, monkeypatch):
+    """The order in which an XCD's workgroups walk the C tiles (the height of its patch of tiles, which
+    the plan reads from ATB_GROUP_M when it is set) decides which tiles share L2, never a value: every
+    patch height, also one that does not divide the 17 tile rows, gives the bits of the default."""
+    M, N, K = 4300, 4400, 136
+    print(f"gemm walk order {tiles}", flush=True)
+    A, Bb = workloads.make_inputs(workloads.CONFIGS["ragged"], M=M, N=N, K=K)
+    mant, expo = oracle.quantize(A)
+    monkeypatch.delenv("ATB_GROUP_M", raising=False)
+    base = _run(mant, expo, Bb, tiles)
+    C_ref, T, _ = oracle.gemm(mant, expo, Bb)
+    _check(base, C_ref, T, f"walk order default {tiles}")
+    for rows in ("1", "3", "1000"):
+        monkeypatch.setenv("ATB_GROUP_M", rows)
+        assert np.array_equal(_run(mant, expo, Bb, tiles), base), f"patch of {rows} tile rows, {tiles}"
+
+
 def test_graph_capture_and_replay():
     """The run call is a single kernel launch on the caller's stream, so a chain of GEMMs and quantisations can be
     captured into a HIP graph (small problems are launch-bound).  Two layers, y = quantise(x W1) W2, captured once
